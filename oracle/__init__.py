@@ -1,0 +1,129 @@
+"""ctypes front end of the fp64 CPU oracle (TEST INFRASTRUCTURE, not the product path).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this package.  It marshals arrays into ``ssa_oracle.c`` and holds no arithmetic of the
+method itself; the definition it calls follows the paper's Eq. 2 / Eq. 4 (Architecture section).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "ssa_oracle.c"
+_LIB = _HERE / "libssa_oracle.so"
+_lib = None
+
+INT64_MAX = (1 << 63) - 1
+
+
+def build(force: bool = False) -> Path:
+    """Compile ssa_oracle.c with gcc (plain C11, -O2, no fast-math)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", str(_LIB), str(_SRC), "-lm", "-lpthread"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.oracle_ssa_rows.restype = ci
+        lib.oracle_ssa_rows.argtypes = [vp, vp, vp, ci, i64, vp, vp, vp, ci, ci, ci, i64, ci, ci,
+                                        i64, i64, i64, i64, ctypes.c_double, vp, vp, vp, ci]
+        lib.oracle_ssa_live_mask.restype = ci
+        lib.oracle_ssa_live_mask.argtypes = [i64, i64, i64, i64, vp]
+        lib.oracle_ssa_count_pairs.restype = i64
+        lib.oracle_ssa_count_pairs.argtypes = [i64, i64, i64]
+        _lib = lib
+    return _lib
+
+
+def host_threads() -> int:
+    """Threads the oracle uses by default: the cores this process may run on."""
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:  # pragma: no cover
+        return max(1, os.cpu_count() or 1)
+
+
+def as_oracle_array(t):
+    """torch tensor / numpy array -> contiguous numpy array the oracle reads (float32, or uint16
+    holding bf16 bit patterns).  The bits are passed through unchanged."""
+    if isinstance(t, np.ndarray):
+        if t.dtype not in (np.float32, np.uint16):
+            raise TypeError(f"oracle reads float32 or bf16-as-uint16, got {t.dtype}")
+        return np.ascontiguousarray(t)
+    import torch
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    if t.dtype == torch.float32:
+        return t.numpy()
+    raise TypeError(f"oracle reads float32 or bfloat16, got {t.dtype}")
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    return 0 if a.dtype == np.float32 else 1
+
+
+def ssa_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, n_sink, window, scale,
+             want_weights=False, n_threads=None):
+    """SSA (Eq. 4) for the listed query rows.
+
+    q_rows [n, d_qk]; k [B, S, Hkv, d_qk]; v [B, S, Hkv, d_v], or ``v=("alias", d_v)`` when the
+    values are the first ``d_v`` columns of the key rows (absorbed MLA: one latent serves both).
+    Returns (out [n, d_v] float64, lse [n] float64[, weights [n, S] float64]).
+    """
+    lib = _load()
+    qa = as_oracle_array(q_rows)
+    ka = as_oracle_array(k)
+    if isinstance(v, tuple) and v[0] == "alias":
+        va, d_v, v_stride = ka, int(v[1]), ka.shape[3]
+    else:
+        va = as_oracle_array(v)
+        d_v, v_stride = va.shape[3], va.shape[3]
+    if not (qa.dtype == ka.dtype == va.dtype):
+        raise TypeError("q, k, v must share a dtype")
+    B, S, Hkv, k_stride = ka.shape
+    n, d_qk = qa.shape
+    rb = np.ascontiguousarray(row_b, dtype=np.int64)
+    rh = np.ascontiguousarray(row_h, dtype=np.int64)
+    ri = np.ascontiguousarray(row_i, dtype=np.int64)
+    assert rb.shape == rh.shape == ri.shape == (n,)
+    out = np.empty((n, d_v), dtype=np.float64)
+    lse = np.empty((n,), dtype=np.float64)
+    w = np.zeros((n, S), dtype=np.float64) if want_weights else None
+    window = min(int(window), INT64_MAX)
+    rc = lib.oracle_ssa_rows(
+        qa.ctypes.data, ka.ctypes.data, va.ctypes.data, _dtype_code(qa), n,
+        rb.ctypes.data, rh.ctypes.data, ri.ctypes.data, B, int(Hq), Hkv, S, d_qk, d_v,
+        k_stride, v_stride, int(n_sink), window, float(scale),
+        out.ctypes.data, lse.ctypes.data, w.ctypes.data if w is not None else None,
+        int(n_threads or host_threads()))
+    if rc != 0:
+        raise RuntimeError(f"oracle_ssa_rows failed with code {rc}")
+    return (out, lse, w) if want_weights else (out, lse)
+
+
+def live_mask(i, S, n_sink, window) -> np.ndarray:
+    """0/1 vector over keys 0..S-1: which keys query i sees."""
+    lib = _load()
+    m = np.zeros((S,), dtype=np.uint8)
+    rc = lib.oracle_ssa_live_mask(int(i), int(S), int(n_sink), min(int(window), INT64_MAX), m.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_ssa_live_mask failed with code {rc}")
+    return m
+
+
+def count_pairs(S, n_sink, window) -> int:
+    """Live (query, key) pairs of a length-S causal prefill, counted one by one."""
+    return int(_load().oracle_ssa_count_pairs(int(S), int(n_sink), min(int(window), INT64_MAX)))

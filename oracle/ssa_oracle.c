@@ -1,0 +1,189 @@
+/*
+ * ssa_oracle.c — TEST INFRASTRUCTURE, not part of the product path.
+ *
+ * Plain, slow, fp64 CPU definition of streaming sparse attention (SSA), written out from the
+ * paper's statement O* = softmax(Q K*) V* (Architecture section, Eq. 2 and Eq. 4): every query
+ * attends to a fixed set of leading "sink" keys plus a causal window of recent keys, and the
+ * softmax is taken over that restricted key set only.  The pieces the paper leaves implicit
+ * (transpose on K, the 1/sqrt(d) scale passed in as `scale`, the normalising denominator, the
+ * causal order of a language model) are written in their textbook form.
+ *
+ * There is no tiling, no online softmax, no range arithmetic and no fusion here: one explicit
+ * alive(i, j) predicate per (query, key) pair, a max, a sum of exponentials, a weighted sum.
+ * The file shares nothing with the GPU library: no header, no table, no helper.
+ *
+ * Only tests/, the smoke check and the CPU-baseline leg of the benchmark may call this.
+ *
+ * Pins (tests/test_oracle_pins.py): hand-enumerated live sets, the paper's own block arithmetic
+ * (1 sink block + 7 local blocks of 128 = 1,024 live tokens, Training section), reduction to
+ * textbook causal attention for window >= S (Eq. 2 -> Eq. 1) checked against an independent
+ * library routine, closed forms for Q = 0 / constant V / single-key rows, shift invariance of
+ * the scores, grouped-head mapping, and brute-force masks built from Python sets.
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_DTYPE_F32 0
+#define ORACLE_DTYPE_BF16 1
+
+/* The sparsity pattern of Eq. 4 at token granularity: key j is visible to query i when it is
+ * not in the future (j <= i) and is either one of the first n_sink keys or one of the `window`
+ * most recent keys, the query's own position included. */
+static int alive(int64_t i, int64_t j, int64_t n_sink, int64_t window)
+{
+    if (j > i) return 0;
+    if (j < n_sink) return 1;
+    /* j > i - window, written without overflow for window up to INT64_MAX */
+    if (i - j < window) return 1;
+    return 0;
+}
+
+/* bf16 is the upper half of an IEEE fp32: widening is exact. */
+static double widen(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == ORACLE_DTYPE_F32) return (double)((const float *)base)[idx];
+    uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+typedef struct {
+    const void *q_rows, *k, *v;
+    int dtype;
+    int64_t n_rows;
+    const int64_t *row_b, *row_h, *row_i;
+    int Hq, Hkv;
+    int64_t S;
+    int d_qk, d_v;
+    int64_t k_row_stride, v_row_stride; /* elements between consecutive (position, kv-head) rows */
+    int64_t n_sink, window;
+    double scale;
+    double *out, *lse, *weights;
+    int64_t next_row; /* shared work counter */
+    int failed;
+} job_t;
+
+/* One query row, straight from the definition. */
+static int one_row(job_t *J, int64_t r, double *score /* S doubles */)
+{
+    const int64_t b = J->row_b[r], h = J->row_h[r], i = J->row_i[r];
+    const int group = J->Hq / J->Hkv;
+    const int64_t g = h / group; /* query head h reads key/value head g */
+    const int64_t S = J->S;
+    int64_t n_alive = 0;
+    double m = -INFINITY;
+
+    for (int64_t j = 0; j < S; ++j) {
+        if (!alive(i, j, J->n_sink, J->window)) { score[j] = -INFINITY; continue; }
+        const int64_t kbase = ((b * S + j) * J->Hkv + g) * J->k_row_stride;
+        double dot = 0.0;
+        for (int c = 0; c < J->d_qk; ++c)
+            dot += widen(J->q_rows, J->dtype, r * (int64_t)J->d_qk + c) * widen(J->k, J->dtype, kbase + c);
+        score[j] = J->scale * dot;
+        if (score[j] > m) m = score[j];
+        ++n_alive;
+    }
+    if (n_alive == 0) return -1; /* softmax over an empty set is undefined */
+
+    double l = 0.0;
+    for (int64_t j = 0; j < S; ++j)
+        if (score[j] != -INFINITY) l += exp(score[j] - m);
+
+    double *o = J->out + r * (int64_t)J->d_v;
+    for (int c = 0; c < J->d_v; ++c) o[c] = 0.0;
+    for (int64_t j = 0; j < S; ++j) {
+        double w = (score[j] == -INFINITY) ? 0.0 : exp(score[j] - m) / l;
+        if (J->weights) J->weights[r * S + j] = w;
+        if (w == 0.0 && score[j] == -INFINITY) continue;
+        const int64_t vbase = ((b * S + j) * J->Hkv + g) * J->v_row_stride;
+        for (int c = 0; c < J->d_v; ++c) o[c] += w * widen(J->v, J->dtype, vbase + c);
+    }
+    J->lse[r] = m + log(l);
+    return 0;
+}
+
+static void *worker(void *arg)
+{
+    job_t *J = (job_t *)arg;
+    double *score = (double *)malloc((size_t)J->S * sizeof(double));
+    if (!score) { __atomic_store_n(&J->failed, 1, __ATOMIC_SEQ_CST); return NULL; }
+    for (;;) {
+        int64_t r = __atomic_fetch_add(&J->next_row, 1, __ATOMIC_SEQ_CST);
+        if (r >= J->n_rows) break;
+        if (one_row(J, r, score) != 0) __atomic_store_n(&J->failed, 2, __ATOMIC_SEQ_CST);
+    }
+    free(score);
+    return NULL;
+}
+
+/*
+ * SSA for a list of query rows (Eq. 4; Eq. 1 when window >= S).
+ *
+ *   q_rows   [n_rows, d_qk]            the query vectors of the listed rows, gathered
+ *   k        [B, S, Hkv, k_row_stride] keys   (first d_qk elements of each row are used)
+ *   v        [B, S, Hkv, v_row_stride] values (first d_v elements of each row are used);
+ *                                      v may alias k (absorbed MLA: V is a prefix of the latent)
+ *   row_b/h/i[n_rows]                  batch index, query head, query position of each row
+ *   out      [n_rows, d_v] fp64, lse [n_rows] fp64 (natural log of the softmax denominator)
+ *   weights  NULL or [n_rows, S] fp64: the attention weights themselves (0 exactly where dead)
+ *
+ * A decode step is the row i = L - 1 of a cache whose rows j >= L are never alive (j > i).
+ * Returns 0, or -1 on a bad argument, -2 if a row has no live key, -3 on allocation failure.
+ */
+int oracle_ssa_rows(const void *q_rows, const void *k, const void *v, int dtype,
+                    int64_t n_rows, const int64_t *row_b, const int64_t *row_h, const int64_t *row_i,
+                    int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                    int64_t k_row_stride, int64_t v_row_stride,
+                    int64_t n_sink, int64_t window, double scale,
+                    double *out, double *lse, double *weights, int n_threads)
+{
+    if (!q_rows || !k || !v || !out || !lse) return -1;
+    if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || d_qk < 1 || d_v < 1) return -1;
+    if (k_row_stride < d_qk || v_row_stride < d_v || n_sink < 0 || window < 1) return -1;
+    for (int64_t r = 0; r < n_rows; ++r)
+        if (row_b[r] < 0 || row_b[r] >= B || row_h[r] < 0 || row_h[r] >= Hq || row_i[r] < 0 || row_i[r] >= S)
+            return -1;
+
+    job_t J;
+    memset(&J, 0, sizeof J);
+    J.q_rows = q_rows; J.k = k; J.v = v; J.dtype = dtype; J.n_rows = n_rows;
+    J.row_b = row_b; J.row_h = row_h; J.row_i = row_i; J.Hq = Hq; J.Hkv = Hkv; J.S = S;
+    J.d_qk = d_qk; J.d_v = d_v; J.k_row_stride = k_row_stride; J.v_row_stride = v_row_stride;
+    J.n_sink = n_sink; J.window = window; J.scale = scale;
+    J.out = out; J.lse = lse; J.weights = weights;
+
+    if (n_threads < 1) n_threads = 1;
+    if (n_threads > 256) n_threads = 256;
+    if ((int64_t)n_threads > n_rows) n_threads = (int)(n_rows > 0 ? n_rows : 1);
+    pthread_t tid[256];
+    int started = 0;
+    for (int t = 1; t < n_threads; ++t)
+        if (pthread_create(&tid[started], NULL, worker, &J) == 0) ++started;
+    worker(&J);
+    for (int t = 0; t < started; ++t) pthread_join(tid[t], NULL);
+    if (J.failed == 1) return -3;
+    if (J.failed == 2) return -2;
+    return 0;
+}
+
+/* The live set of one query as an explicit 0/1 vector over keys 0..S-1 (Eq. 4's pattern). */
+int oracle_ssa_live_mask(int64_t i, int64_t S, int64_t n_sink, int64_t window, uint8_t *mask)
+{
+    if (!mask || S < 1 || i < 0 || i >= S || n_sink < 0 || window < 1) return -1;
+    for (int64_t j = 0; j < S; ++j) mask[j] = (uint8_t)alive(i, j, n_sink, window);
+    return 0;
+}
+
+/* Number of live (query, key) pairs of a causal length-S prefill, by counting them one by one. */
+int64_t oracle_ssa_count_pairs(int64_t S, int64_t n_sink, int64_t window)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < S; ++i)
+        for (int64_t j = 0; j <= i; ++j) n += alive(i, j, n_sink, window);
+    return n;
+}
