@@ -1,0 +1,114 @@
+/*
+ * loza_ssa.h — C ABI of the streaming sparse attention (SSA) library for MI355X (gfx950).
+ *
+ * SSA is the sparse attention of LongCat ZigZag Attention: O* = softmax(Q K*^T) V*, where every
+ * query keeps a fixed set of leading "sink" keys plus a causal window of its most recent keys
+ * (paper: Architecture section, Eq. 2 and Eq. 4; sink/local sizes in the Training section).
+ * With window >= S the same entry points compute ordinary causal attention (Eq. 1), which is the
+ * full-attention comparator.
+ *
+ * Live set at token granularity (0-based query position i, key position j):
+ *     live(i) = { j : j <= i  and ( j < n_sink  or  i - j < window ) }
+ * so the window counts the query's own position, sink and window are united (a key is used once),
+ * and |live(i)| = min(i + 1, n_sink + window).
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers unless stated; the caller owns every buffer; the
+ *     library allocates nothing, keeps no state between calls and performs no host sync.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls are
+ *     asynchronous on it.
+ *   - Layouts are dense, innermost index fastest. bf16 tensors are raw 16-bit patterns.
+ *   - Query head h reads key/value head h / (Hq / Hkv); Hq must be a multiple of Hkv.
+ *   - Absorbed MLA (many query heads share one latent): pass v == k with d_v <= d_qk; the value
+ *     row is then the first d_v elements of the key row (row stride d_qk) and costs no second load.
+ *   - Base pointers must be 16-byte aligned. Inputs must be finite.
+ *   - Every argument is validated before the first HIP call; a failed validation launches nothing.
+ *   - Return value: LOZA_OK or a negative loza_status.
+ */
+#ifndef LOZA_SSA_H
+#define LOZA_SSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOZA_OK = 0,
+    LOZA_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+    LOZA_ERR_SHAPE = -2,       /* sizes out of range or inconsistent (Hq % Hkv, window < 1…)  */
+    LOZA_ERR_UNSUPPORTED = -3, /* a (dtype, d_qk, d_v) combination no kernel is built for      */
+    LOZA_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than loza_ssa_decode_workspace_bytes */
+    LOZA_ERR_HIP = -5,         /* a HIP call failed (hipGetLastError has the detail)          */
+    LOZA_ERR_ALIGN = -6        /* a base pointer is not 16-byte aligned                       */
+} loza_status;
+
+#define LOZA_WINDOW_INF INT64_MAX /* window = infinity: full causal attention (Eq. 1) */
+
+/*
+ * SSA prefill, bf16 in / bf16 out, fp32 accumulation (Eq. 4; Eq. 1 when window >= S).
+ *   q    [B, S, Hq,  d_qk] bf16      k [B, S, Hkv, d_qk] bf16      v [B, S, Hkv, d_v] bf16 (or v == k)
+ *   out  [B, S, Hq,  d_v ] bf16      lse [B, Hq, S] fp32, natural log of the softmax denominator
+ *   n_sink >= 0 leading keys always visible; window >= 1 most recent keys visible (self included).
+ *   scale multiplies q.k before the softmax (the 1/sqrt(d) the paper's equations leave out).
+ * Supported (d_qk, d_v): (576, 512) with Hkv == 1 and v == k (absorbed MLA), (128, 128), (64, 64).
+ * S <= 2^31 - 129.
+ */
+int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                     int64_t n_sink, int64_t window, float scale, void *stream);
+
+/*
+ * fp32 twin of loza_ssa_prefill (fp32 in, fp32 arithmetic, fp32 out), same layouts with float
+ * elements. Any d_qk, d_v in [1, 256]; v may alias k with d_v <= d_qk.
+ */
+int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                         int64_t n_sink, int64_t window, float scale, void *stream);
+
+/*
+ * SSA decode: one new query token per sequence against that sequence's KV cache (the decode
+ * kernel of the paper's Efficiency section). Split over the live keys with a log-sum-exp merge.
+ *   q       [B, Hq, d_qk] bf16
+ *   kcache  [B, S_max, Hkv, d_qk] bf16     vcache [B, S_max, Hkv, d_v] bf16 (or vcache == kcache)
+ *   seqlens [B] int32 (device): valid rows of each cache INCLUDING the new token's own key/value,
+ *           so the query sits at position seqlens[b] - 1. 0 <= seqlens[b] <= S_max is required;
+ *           a sequence of length 0 yields out = 0, lse = -inf.
+ *   out     [B, Hq, d_v] bf16              lse [B, Hq] fp32
+ *   workspace: device scratch of at least loza_ssa_decode_workspace_bytes(...) bytes, 16-byte
+ *           aligned; contents on entry are ignored, on exit unspecified.
+ * Supported (d_qk, d_v): as loza_ssa_prefill. Cache rows at or beyond seqlens[b] are never read.
+ */
+int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                    void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                    int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only. Bytes of workspace loza_ssa_decode needs for these sizes (0 on invalid sizes). */
+size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, int d_v,
+                                       int64_t n_sink, int64_t window);
+
+/* Host-only. Number of key splits loza_ssa_decode uses for these sizes (0 on invalid sizes). */
+int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window);
+
+/*
+ * Host-only, no GPU involved: the live set of query i as at most two half-open key ranges,
+ * [0, *sink_end) and [*win_begin, *win_end), disjoint and in order (sink_end <= win_begin).
+ * This is the arithmetic the kernels enumerate tiles with (Eq. 4's pattern, "single uniform
+ * schedule" of the Desiderata section: no per-head metadata).
+ */
+int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
+                         int64_t *sink_end, int64_t *win_begin, int64_t *win_end);
+
+/* Host-only. Live (query, key) pairs of a causal length-S prefill: sum over i of |live(i)|. */
+int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window);
+
+/* Host-only. Static string naming a status code. */
+const char *loza_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOZA_SSA_H */

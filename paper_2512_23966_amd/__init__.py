@@ -1,0 +1,11 @@
+"""MI355X-native streaming sparse attention (the SSA hot path of LongCat ZigZag Attention).
+
+The product is ``libloza_ssa.so`` (hand-written HIP for gfx950 behind the C ABI of
+``include/loza_ssa.h``); this package is its Python binding plus the synthetic workload recipes.
+"""
+from .binding import (  # noqa: F401
+    LIB_PATH, LOZA_OK, LOZA_WINDOW_INF, EXPORTS, LozaError, lib,
+    loza_ssa_prefill, loza_ssa_prefill_f32, loza_ssa_decode,
+    loza_ssa_decode_workspace_bytes, loza_ssa_decode_num_splits,
+    loza_ssa_live_ranges, loza_ssa_live_pairs, loza_status_str,
+)

@@ -1,0 +1,155 @@
+"""Thin ctypes binding of ``libloza_ssa.so``: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point (``include/loza_ssa.h``).
+Tensors are torch tensors that already live on the GPU; nothing is computed here and there is no
+fallback: if the shared library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libloza_ssa.so"
+_lib = None
+
+LOZA_OK = 0
+LOZA_WINDOW_INF = (1 << 63) - 1
+
+EXPORTS = (
+    "loza_ssa_prefill", "loza_ssa_prefill_f32", "loza_ssa_decode",
+    "loza_ssa_decode_workspace_bytes", "loza_ssa_decode_num_splits",
+    "loza_ssa_live_ranges", "loza_ssa_live_pairs", "loza_status_str",
+)
+
+
+class LozaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {loza_status_str(status)} ({status})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (built beforehand by ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(str(LIB_PATH))
+        vp, ci, i64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+        L.loza_ssa_prefill.restype = ci
+        L.loza_ssa_prefill.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_prefill_f32.restype = ci
+        L.loza_ssa_prefill_f32.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_decode.restype = ci
+        L.loza_ssa_decode.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_decode_workspace_bytes.restype = sz
+        L.loza_ssa_decode_workspace_bytes.argtypes = [ci, ci, ci, i64, ci, i64, i64]
+        L.loza_ssa_decode_num_splits.restype = ci
+        L.loza_ssa_decode_num_splits.argtypes = [ci, ci, ci, i64, i64, i64]
+        L.loza_ssa_live_ranges.restype = ci
+        L.loza_ssa_live_ranges.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.loza_ssa_live_pairs.restype = i64
+        L.loza_ssa_live_pairs.argtypes = [i64, i64, i64]
+        L.loza_status_str.restype = ctypes.c_char_p
+        L.loza_status_str.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def _win(window) -> int:
+    return LOZA_WINDOW_INF if window is None else min(int(window), LOZA_WINDOW_INF)
+
+
+def _dev_ptr(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a tensor on the GPU")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def loza_status_str(status: int) -> str:
+    return lib().loza_status_str(int(status)).decode()
+
+
+def loza_ssa_live_ranges(i: int, n_sink: int, window):
+    """(sink_end, win_begin, win_end): live(i) = [0, sink_end) U [win_begin, win_end). Host only."""
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = lib().loza_ssa_live_ranges(int(i), int(n_sink), _win(window), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_live_ranges")
+    return a.value, b.value, c.value
+
+
+def loza_ssa_live_pairs(S: int, n_sink: int, window) -> int:
+    return int(lib().loza_ssa_live_pairs(int(S), int(n_sink), _win(window)))
+
+
+def _prefill_common(fn_name, dtype, q, k, v, out, lse, n_sink, window, scale, stream):
+    B, S, Hq, d_qk = q.shape
+    Hkv = k.shape[2]
+    d_v = out.shape[3]
+    if k.shape != (B, S, Hkv, d_qk) or out.shape != (B, S, Hq, d_v) or lse.shape != (B, Hq, S):
+        raise ValueError("shape mismatch between q, k, out, lse")
+    if v is not k and v.shape != (B, S, Hkv, d_v):
+        raise ValueError("v must be [B, S, Hkv, d_v] (or the very tensor passed as k)")
+    qp, kp = _dev_ptr(q, dtype, "q"), _dev_ptr(k, dtype, "k")
+    vp = kp if v is k else _dev_ptr(v, dtype, "v")
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(out, dtype, "out"), _dev_ptr(lse, torch.float32, "lse"),
+                                 B, Hq, Hkv, S, d_qk, d_v, int(n_sink), _win(window), float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_prefill(q, k, v, out, lse, n_sink, window, scale, stream=None):
+    """bf16 SSA prefill. q [B,S,Hq,d_qk], k [B,S,Hkv,d_qk], v [B,S,Hkv,d_v] or ``v is k`` (absorbed
+    MLA: values are the first d_v columns of k), out [B,S,Hq,d_v] bf16, lse [B,Hq,S] fp32.
+    ``window=None`` means infinity (full causal attention)."""
+    _prefill_common("loza_ssa_prefill", torch.bfloat16, q, k, v, out, lse, n_sink, window, scale, stream)
+
+
+def loza_ssa_prefill_f32(q, k, v, out, lse, n_sink, window, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_prefill`."""
+    _prefill_common("loza_ssa_prefill_f32", torch.float32, q, k, v, out, lse, n_sink, window, scale, stream)
+
+
+def loza_ssa_decode_num_splits(B, Hq, Hkv, S_max, n_sink, window) -> int:
+    return int(lib().loza_ssa_decode_num_splits(B, Hq, Hkv, int(S_max), int(n_sink), _win(window)))
+
+
+def loza_ssa_decode_workspace_bytes(B, Hq, Hkv, S_max, d_v, n_sink, window) -> int:
+    return int(lib().loza_ssa_decode_workspace_bytes(B, Hq, Hkv, int(S_max), d_v, int(n_sink), _win(window)))
+
+
+def loza_ssa_decode(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, workspace, stream=None):
+    """bf16 SSA decode. q [B,Hq,d_qk], kcache [B,S_max,Hkv,d_qk], vcache [B,S_max,Hkv,d_v] or
+    ``vcache is kcache``, seqlens [B] int32 on the GPU, out [B,Hq,d_v] bf16, lse [B,Hq] fp32,
+    workspace: uint8 GPU tensor of at least ``loza_ssa_decode_workspace_bytes`` bytes."""
+    B, Hq, d_qk = q.shape
+    _, S_max, Hkv, _ = kcache.shape
+    d_v = out.shape[2]
+    if kcache.shape != (B, S_max, Hkv, d_qk) or out.shape != (B, Hq, d_v) or lse.shape != (B, Hq) or seqlens.shape != (B,):
+        raise ValueError("shape mismatch between q, kcache, seqlens, out, lse")
+    if vcache is not kcache and vcache.shape != (B, S_max, Hkv, d_v):
+        raise ValueError("vcache must be [B, S_max, Hkv, d_v] (or the very tensor passed as kcache)")
+    bf = torch.bfloat16
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(kcache, bf, "kcache")
+    vp = kp if vcache is kcache else _dev_ptr(vcache, bf, "vcache")
+    wp = _dev_ptr(workspace, torch.uint8, "workspace")
+    rc = lib().loza_ssa_decode(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                               _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, S_max, d_qk, d_v,
+                               int(n_sink), _win(window), float(scale), wp, workspace.numel(), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_decode")

@@ -1,0 +1,185 @@
+// C ABI of the SSA library: argument validation, host-side schedule arithmetic, dispatch.
+// Every check runs before the first HIP call, so a rejected call launches nothing.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "../../include/loza_ssa.h"
+#include "ssa_kernels.h"
+
+namespace {
+
+constexpr int kComputeUnits = 256;              // MI355X
+constexpr int64_t kMaxSeq = 2147483647LL - 128;  // positions are 32-bit inside the kernels
+
+inline bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
+
+// window / n_sink cut to what can matter for sequences of at most S keys
+inline int clamp_to(int64_t x, int64_t S) { return (int)(x < S ? x : S); }
+
+int check_common(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v, int64_t n_sink, int64_t window, float scale)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || S < 1 || d_qk < 1 || d_v < 1) return LOZA_ERR_SHAPE;
+    if (Hq % Hkv != 0) return LOZA_ERR_SHAPE;
+    if (S > kMaxSeq) return LOZA_ERR_SHAPE;
+    if (n_sink < 0 || window < 1) return LOZA_ERR_SHAPE;
+    if (!(scale == scale) || isinf(scale)) return LOZA_ERR_SHAPE;
+    return LOZA_OK;
+}
+
+int decode_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window)
+{
+    const int G = Hq / Hkv;
+    const int rows = loza::decode_rows_per_tile();
+    const int64_t base = (int64_t)B * Hkv * ((G + rows - 1) / rows);
+    int64_t live = n_sink + (window < S_max ? window : S_max);
+    if (live > S_max) live = S_max;
+    const int64_t tiles = (live + 63) / 64 + 2;
+    int64_t n = (kComputeUnits + base - 1) / base;  // one workgroup per compute unit at least
+    if (const char *env = getenv("LOZA_DECODE_SPLITS")) {
+        const long v = strtol(env, nullptr, 10);
+        if (v >= 1) n = v;
+    }
+    if (n > tiles) n = tiles;
+    if (n > 64) n = 64;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *loza_status_str(int status)
+{
+    switch (status) {
+    case LOZA_OK: return "LOZA_OK";
+    case LOZA_ERR_NULL: return "LOZA_ERR_NULL: a required pointer is NULL";
+    case LOZA_ERR_SHAPE: return "LOZA_ERR_SHAPE: sizes out of range or inconsistent";
+    case LOZA_ERR_UNSUPPORTED: return "LOZA_ERR_UNSUPPORTED: no kernel for this (dtype, d_qk, d_v)";
+    case LOZA_ERR_WORKSPACE: return "LOZA_ERR_WORKSPACE: workspace missing or too small";
+    case LOZA_ERR_HIP: return "LOZA_ERR_HIP: a HIP call failed";
+    case LOZA_ERR_ALIGN: return "LOZA_ERR_ALIGN: a base pointer is not 16-byte aligned";
+    default: return "unknown loza status";
+    }
+}
+
+int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
+                         int64_t *sink_end, int64_t *win_begin, int64_t *win_end)
+{
+    if (!sink_end || !win_begin || !win_end) return LOZA_ERR_NULL;
+    if (i < 0 || n_sink < 0 || window < 1) return LOZA_ERR_SHAPE;
+    const int64_t se = n_sink < i + 1 ? n_sink : i + 1;
+    int64_t wb = window > i ? 0 : i - window + 1;
+    if (wb < se) wb = se;  // a key in both sets is used once
+    *sink_end = se;
+    *win_begin = wb;
+    *win_end = i + 1;
+    return LOZA_OK;
+}
+
+int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
+{
+    if (S < 1 || n_sink < 0 || window < 1) return -1;
+    // |live(i)| = min(i + 1, T), T = n_sink + window (saturating)
+    const int64_t T = (window >= S || n_sink >= S || n_sink + window >= S) ? S : n_sink + window;
+    return T * (T + 1) / 2 + (S - T) * T;
+}
+
+int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                     int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale)) return rc;
+    const bool alias = (v == k);
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return LOZA_ERR_ALIGN;
+    const int G = Hq / Hkv;
+    const int rows = loza::prefill_rows_per_tile();
+    const int64_t row_tiles = (S * G + rows - 1) / rows;
+    if (row_tiles * Hkv * B > 2147483647LL) return LOZA_ERR_SHAPE;
+
+    loza::FwdParams p{};
+    p.q = (const uint16_t *)q; p.k = (const uint16_t *)k; p.v = (const uint16_t *)v;
+    p.out = (uint16_t *)out; p.lse = lse;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S;
+    p.n_sink = clamp_to(n_sink, S); p.window = clamp_to(window, S);
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    p.row_tiles = (int)row_tiles; p.n_splits = 1;
+    return loza::launch_prefill_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                         int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale)) return rc;
+    const bool alias = (v == k);
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (d_qk > 256 || d_v > 256) return LOZA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return LOZA_ERR_ALIGN;
+    if (((int64_t)B * S * Hq + 3) / 4 > 2147483647LL) return LOZA_ERR_SHAPE;
+
+    loza::F32Params p{};
+    p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.d_qk = d_qk; p.d_v = d_v;
+    p.k_row = d_qk; p.v_row = alias ? d_qk : d_v;
+    p.n_sink = clamp_to(n_sink, S); p.window = clamp_to(window, S);
+    p.scale = scale;
+    return loza::launch_prefill_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window)
+{
+    if (check_common(B, Hq, Hkv, S_max, 1, 1, n_sink, window, 1.0f) != LOZA_OK) return 0;
+    return decode_splits(B, Hq, Hkv, S_max, n_sink, window);
+}
+
+size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, int d_v,
+                                       int64_t n_sink, int64_t window)
+{
+    if (d_v < 1) return 0;
+    const int n = loza_ssa_decode_num_splits(B, Hq, Hkv, S_max, n_sink, window);
+    if (n == 0) return 0;
+    return (size_t)B * Hq * n * ((size_t)d_v + 2) * sizeof(float);
+}
+
+int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                    void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                    int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
+    if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, scale)) return rc;
+    const bool alias = (vcache == kcache);
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;
+    const size_t need = loza_ssa_decode_workspace_bytes(B, Hq, Hkv, S_max, d_v, n_sink, window);
+    if (!workspace || workspace_bytes < need) return LOZA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(kcache) || !aligned16(vcache) || !aligned16(out) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(seqlens) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return LOZA_ERR_ALIGN;
+    const int G = Hq / Hkv;
+    const int rows = loza::decode_rows_per_tile();
+    const int n_splits = decode_splits(B, Hq, Hkv, S_max, n_sink, window);
+    const int64_t row_tiles = (G + rows - 1) / rows;
+    if (row_tiles * Hkv * B * n_splits > 2147483647LL) return LOZA_ERR_SHAPE;
+
+    loza::FwdParams p{};
+    p.q = (const uint16_t *)q; p.k = (const uint16_t *)kcache; p.v = (const uint16_t *)vcache;
+    p.out = (uint16_t *)out; p.lse = lse;
+    p.part_o = (float *)workspace;
+    p.part_ml = (float *)workspace + (size_t)B * Hq * n_splits * d_v;
+    p.seqlens = seqlens;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S_max;
+    p.n_sink = clamp_to(n_sink, S_max); p.window = clamp_to(window, S_max);
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    p.row_tiles = (int)row_tiles; p.n_splits = n_splits;
+    return loza::launch_decode_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+}  // extern "C"

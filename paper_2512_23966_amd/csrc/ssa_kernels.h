@@ -1,0 +1,47 @@
+// Internal interface between the C-ABI translation unit and the kernel translation units.
+#ifndef LOZA_SSA_KERNELS_H
+#define LOZA_SSA_KERNELS_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace loza {
+
+// Arguments of the bf16 forward kernels. `S` is the sequence length of a prefill, or the row
+// count (stride) of each sequence's cache in a decode. n_sink and window are already cut to
+// [0, S] by the host (a window of S keys or more is "infinite").
+struct FwdParams {
+    const uint16_t *q, *k, *v;
+    uint16_t *out;
+    float *lse;
+    float *part_o;   // decode: [B, Hq, n_splits, d_v] unnormalised partial outputs
+    float *part_ml;  // decode: [B, Hq, n_splits, 2]   running max (log2 domain), partial sum
+    const int32_t *seqlens;
+    int B, Hq, Hkv, G;
+    int64_t S;
+    int n_sink, window;
+    float scale_log2;  // scale * log2(e)
+    int row_tiles;     // workgroup tiles per (batch, kv head)
+    int n_splits;      // decode only
+};
+
+bool bf16_shape_supported(int d_qk, int d_v, bool alias);
+int prefill_rows_per_tile();
+int decode_rows_per_tile();
+hipError_t launch_prefill_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
+hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
+
+struct F32Params {
+    const float *q, *k, *v;
+    float *out, *lse;
+    int B, Hq, Hkv;
+    int64_t S;
+    int d_qk, d_v;
+    int64_t k_row, v_row;  // elements per key / value row (v_row = d_qk when v aliases k)
+    int n_sink, window;
+    float scale;
+};
+hipError_t launch_prefill_f32(const F32Params &p, hipStream_t stream);
+
+}  // namespace loza
+#endif
