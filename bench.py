@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSA hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+  * the 128K-token absorbed-MLA SSA prefill (64 query heads on one 576-wide latent, n_sink 128,
+    window 8192), and
+  * one SSA decode step for 64 sequences with cache lengths uniform in [65536, 262144].
+Inputs are resident in HBM before the timed region. The printed JSON line carries the whole-step
+throughput in effective TFLOP/s (2*(d_qk+d_v) FLOP per live (query, key, head) pair, live pairs
+only), the live-measured roofline of the prefill kernel (bf16 MFMA) and of the decode kernel
+(HBM), the speed-up over the same kernels run with window = infinity, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparator", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2512_23966_amd as loza
+    from paper_2512_23966_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    loza.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    pc, dc = W.CFG3, W.CFG4
+
+    # ---- inputs, resident in HBM ---------------------------------------------------------------
+    q, k, v = W.make_prefill_inputs(pc, dev)
+    out = torch.empty(pc.B, pc.S, pc.Hq, pc.d_v, dtype=pc.dtype, device=dev)
+    lse = torch.empty(pc.B, pc.Hq, pc.S, dtype=torch.float32, device=dev)
+    dq, kc, vc, seqlens = W.make_decode_inputs(dc, dev)
+    dout = torch.empty(dc.B, dc.Hq, dc.d_v, dtype=torch.bfloat16, device=dev)
+    dlse = torch.empty(dc.B, dc.Hq, dtype=torch.float32, device=dev)
+    ws = torch.empty(loza.loza_ssa_decode_workspace_bytes(dc.B, dc.Hq, dc.Hkv, dc.S_max, dc.d_v, dc.n_sink, dc.window),
+                     dtype=torch.uint8, device=dev)
+    seqlens_host = seqlens.cpu().numpy().astype(np.int64)
+
+    def prefill(window=pc.window):
+        loza.loza_ssa_prefill(q, k, v, out, lse, pc.n_sink, window, pc.scale)
+
+    def decode(window=dc.window):
+        loza.loza_ssa_decode(dq, kc, vc, seqlens, dout, dlse, dc.n_sink, window, dc.scale, ws)
+
+    # ---- algorithmic work per launch --------------------------------------------------------------
+    prefill_flop = 2.0 * loza.loza_ssa_live_pairs(pc.S, pc.n_sink, pc.window) * (pc.d_qk + pc.d_v) * pc.Hq * pc.B
+    live_rows = np.minimum(seqlens_host, dc.n_sink + dc.window)
+    decode_flop = 2.0 * float(live_rows.sum()) * (dc.d_qk + dc.d_v) * dc.Hq
+    # decode bytes: every live cache row once (values alias the keys), queries, outputs, lse
+    decode_bytes = float(live_rows.sum()) * dc.d_qk * 2 + dq.numel() * 2 + dout.numel() * 2 + dlse.numel() * 4
+
+    # ---- timed region --------------------------------------------------------------------------------
+    for _ in range(args.warmup):
+        prefill(); decode()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        prefill()
+        ev[s][1].record()
+        decode()
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    prefill_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    decode_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    value = (prefill_flop + decode_flop) / (ms_per_step * 1e-3) / 1e12
+    prefill_tflops = prefill_flop / (prefill_ms * 1e-3) / 1e12
+    decode_gbps = decode_bytes / (decode_ms * 1e-3) / 1e9
+
+    # ---- counters measured with rocprofv3 --pmc (stored summaries), if present ------------------
+    traffic = {"prefill": None, "decode": None}
+    tfile = ROOT / "profiles" / "hbm_traffic.json"
+    if tfile.exists():
+        try:
+            traffic.update(json.loads(tfile.read_text()))
+        except Exception:
+            pass
+
+    result = {
+        "metric": "SSA prefill eff. TFLOP/s + decode HBM GB/s; speedup vs full attn @128K",
+        "value": round(value, 2),
+        "unit": "TFLOP/s (effective, live pairs only; decode GB/s in decode_gbps)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "MLA absorbed SSA prefill bf16 B=1 Hq=64 Hkv=1 S=131072 d_qk=576 d_v=512 n_sink=128 window=8192 "
+                        "+ MLA SSA decode bf16 B=64 Hq=64 cache lengths U[65536,262144] (one step = one prefill + one decode)",
+            "prefill": pc.name, "decode": dc.name,
+        },
+        "prefill_ms": round(prefill_ms, 4),
+        "prefill_tflops": round(prefill_tflops, 2),
+        "decode_us": round(decode_ms * 1e3, 2),
+        "decode_gbps": round(decode_gbps, 1),
+        "decode_num_splits": loza.loza_ssa_decode_num_splits(dc.B, dc.Hq, dc.Hkv, dc.S_max, dc.n_sink, dc.window),
+        "roofline": {
+            "kernel": "ssa_fwd_kernel<576,512> prefill", "bound": "mfma",
+            "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic["prefill"],
+        },
+        "roofline_decode": {
+            "kernel": "ssa_fwd_kernel<576,512> decode split + merge", "bound": "hbm",
+            "achieved": round(decode_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(decode_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic["decode"],
+        },
+    }
+
+    # ---- the same kernels as full attention (window = infinity) -------------------------------------
+    if not args.no_comparator:
+        def timed(fn, reps):
+            fn(); torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record(); torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        full_prefill_ms = timed(lambda: prefill(None), 1)
+        ws_full = torch.empty(loza.loza_ssa_decode_workspace_bytes(dc.B, dc.Hq, dc.Hkv, dc.S_max, dc.d_v, dc.n_sink, None),
+                              dtype=torch.uint8, device=dev)
+
+        def decode_full():
+            loza.loza_ssa_decode(dq, kc, vc, seqlens, dout, dlse, dc.n_sink, None, dc.scale, ws_full)
+        full_decode_ms = timed(decode_full, 3)
+        result["full_attention"] = {
+            "prefill_ms": round(full_prefill_ms, 3), "prefill_speedup": round(full_prefill_ms / prefill_ms, 2),
+            "decode_us": round(full_decode_ms * 1e3, 1), "decode_speedup": round(full_decode_ms / decode_ms, 2),
+            "decode_gbps": round((float(seqlens_host.sum()) * dc.d_qk * 2) / (full_decode_ms * 1e-3) / 1e9, 1),
+        }
+
+    # ---- CPU oracle on a bounded sample of the same prefill workload ----------------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.host_threads()
+        k_host = k.cpu()
+        rng = np.random.default_rng(0)
+
+        def run_sample(n):
+            ri = rng.integers(pc.n_sink + pc.window, pc.S, size=n).astype(np.int64)  # rows with the full live set
+            rh = rng.integers(0, pc.Hq, size=n).astype(np.int64)
+            rb = np.zeros(n, dtype=np.int64)
+            q_rows = q[0, torch.as_tensor(ri, device=dev), torch.as_tensor(rh, device=dev)].cpu()
+            t = time.perf_counter()
+            oracle.ssa_rows(q_rows, k_host, ("alias", pc.d_v), rb, rh, ri, Hq=pc.Hq, n_sink=pc.n_sink,
+                            window=pc.window, scale=pc.scale, n_threads=threads)
+            return time.perf_counter() - t
+        t_cal = run_sample(4 * threads)
+        n = int(min(32768, max(4 * threads, 12.0 / (t_cal / (4 * threads)))))
+        t_cpu = run_sample(n)
+        cpu_flop = 2.0 * n * (pc.n_sink + pc.window) * (pc.d_qk + pc.d_v)
+        result["cpu_baseline"] = {
+            "value": round(cpu_flop / t_cpu / 1e12, 6), "unit": "TFLOP/s (effective, same FLOP formula)",
+            "cores": threads, "kind": "oracle",
+            "sample": f"{n} seeded random (position, head) rows of the 128K prefill with the full {pc.n_sink + pc.window}-key live set, "
+                      f"{t_cpu:.1f} s; whole prefill would take {prefill_flop / (cpu_flop / t_cpu) / 3600:.1f} h",
+        }
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
