@@ -145,7 +145,7 @@ size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, in
     if (d_v < 1) return 0;
     const int n = loza_ssa_decode_num_splits(B, Hq, Hkv, S_max, n_sink, window);
     if (n == 0) return 0;
-    return (size_t)B * Hq * n * ((size_t)d_v + 2) * sizeof(float);
+    return (size_t)B * Hq * n * ((size_t)d_v + 4) * sizeof(float);
 }
 
 int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,

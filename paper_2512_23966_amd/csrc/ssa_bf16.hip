@@ -76,35 +76,50 @@ struct TileCfg {
     static constexpr int VROW = ALIAS ? KROW : DV * 2 + 16;
     static constexpr int KCPR = KROW / 16;       // 16-byte chunks per padded key row
     static constexpr int VCPR = VROW / 16;
-    static constexpr int KTILE = N * KROW;
-    static constexpr int VTILE = ALIAS ? 0 : N * VROW;
-    static constexpr int STAGE = KTILE + VTILE;
-    static constexpr int NSTAGE = 2;
-    static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
-    static constexpr int OFF_P = NSTAGE * STAGE;
-    static constexpr int OFF_ALPHA = OFF_P + M * PROW;        // float[M]
-    static constexpr int OFF_FLAG = OFF_ALPHA + M * 4;        // int[RB] (padded to 16)
-    static constexpr int OFF_SMAX = OFF_FLAG + 16;            // float[KB][M]
-    static constexpr int OFF_LPART = OFF_SMAX + KB * M * 4;   // float[KB][M]
-    static constexpr int LDS_BYTES = OFF_LPART + KB * M * 4;
-    static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
-    // global -> LDS copy: one instruction moves 64 consecutive 16-byte chunks of the padded tile
+    // global -> LDS copy: one instruction moves 64 consecutive 16-byte chunks (1 KB) of the padded
+    // tile; instruction i belongs to wave i % 4
     static constexpr int K_INSTR = (N * KCPR + 63) / 64;
     static constexpr int V_INSTR = ALIAS ? 0 : (N * VCPR + 63) / 64;
     static constexpr int K_PER_WAVE = (K_INSTR + NW - 1) / NW;
     static constexpr int V_PER_WAVE = (V_INSTR + NW - 1) / NW;
+    static constexpr int KTILE = K_INSTR * 1024;
+    static constexpr int VTILE = V_INSTR * 1024;
+    static constexpr int STAGE = KTILE + VTILE;
+    // KB == 1 (prefill): software pipeline over three tile stages and two P buffers;
+    // KB == 2 (decode): two stages, one P buffer
+    static constexpr bool PIPE = (KB == 1);
+    static constexpr int NSTAGE = PIPE ? 3 : 2;
+    static constexpr int NPBUF = PIPE ? 2 : 1;
+    static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
+    static constexpr int PBYTES = M * PROW;
+    static constexpr int OFF_P = NSTAGE * STAGE;
+    static constexpr int OFF_ALPHA = OFF_P + NPBUF * PBYTES;      // float[NPBUF][M]
+    static constexpr int OFF_FLAG = OFF_ALPHA + NPBUF * M * 4;    // int[NPBUF][4]
+    static constexpr int OFF_SMAX = OFF_FLAG + NPBUF * 16;        // float[KB][M]
+    static constexpr int OFF_LPART = OFF_SMAX + KB * M * 4;       // float[2][KB][M]
+    static constexpr int LDS_BYTES = OFF_LPART + 2 * KB * M * 4;
+    static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
-// One lane's share of one copy instruction: (row in tile, chunk in row) or "idle".
-static __device__ __forceinline__ int chunk_code(int instr, int n_instr, int lane, int rows, int cpr)
+// Byte offset, inside a key tile in global memory, of the 16-byte chunk that lane `lane` of copy
+// instruction `instr` moves. LDS slot p = instr*64 + lane is chunk (p % cpr) of padded row
+// (p / cpr); padding slots and slots past the tile fetch some valid chunk (never read back).
+static __device__ __forceinline__ uint32_t chunk_offset(int instr, int lane, int rows, int cpr, uint32_t pos_stride)
 {
-    if (instr >= n_instr) return -1;
     const int p = instr * 64 + lane;
-    if (p >= rows * cpr) return -1;
-    const int row = p / cpr, c = p - row * cpr;
-    if (c == cpr - 1) return -1;  // the padding chunk of a row
-    return row | (c << 8);
+    int row = p / cpr, c = p - row * cpr;
+    row = row < rows ? row : rows - 1;
+    c = c < cpr - 1 ? c : cpr - 2;
+    return (uint32_t)row * pos_stride + (uint32_t)c * 16u;
 }
+
+// After the first LOZA_EXACT_MAX_TILES tiles of a row, the reference maximum is only moved when the
+// tile maximum exceeds it by more than LOZA_LAZY_RESCALE_LOG2 (log2 units): the accumulator rescale
+// then almost never runs, and P stays below 2^8. Over the first tiles the reference is the exact
+// running maximum, so that the dominant weight of a row with few live keys (where the output is
+// large) is exactly 1 and carries no bf16 rounding error.
+#define LOZA_LAZY_RESCALE_LOG2 8.0f
+#define LOZA_EXACT_MAX_TILES 8
 
 template <int DQK, int DV, int RB, int KB, bool ALIAS, bool DECODE>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
@@ -114,7 +129,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, lh = lane >> 5;
     const int wr = wave / KB, wk = wave % KB;
 
     // ---- which tile of which (batch, kv head) ------------------------------------------------
@@ -140,8 +155,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + r0 + r;
             float *po = p.part_o + (h * p.n_splits + split) * DV;
             for (int c = 0; c < DV; ++c) po[c] = 0.f;
-            p.part_ml[(h * p.n_splits + split) * 2 + 0] = LOZA_NEG_INF;
-            p.part_ml[(h * p.n_splits + split) * 2 + 1] = 0.f;
+            p.part_ml[(h * p.n_splits + split) * 4 + 0] = LOZA_NEG_INF;
+            p.part_ml[(h * p.n_splits + split) * 4 + 1] = 0.f;
+            p.part_ml[(h * p.n_splits + split) * 4 + 2] = 0.f;
         }
         return;
     }
@@ -177,47 +193,73 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         t_begin = split * per;
         t_end = t_begin + per < n_tiles ? t_begin + per : n_tiles;
     }
+    auto key_tile = [&](int t) { return t < nA ? t : wt0 + (t - nA); };
 
-    // ---- global -> LDS copy plan of this lane (the same for every tile) --------------------------
-    int kcode[C::K_PER_WAVE];
+    auto lane16_of = [](int l) { return (uint32_t)l * 16u; };
+    // ---- global -> LDS copy plan (the same for every tile) --------------------------------------
+    // Copy instruction `instr` fills LDS slots [instr*64, instr*64 + 64) of the padded tile: slot p
+    // is chunk p % cpr of row p / cpr. Within one instruction the row changes at most once, at lane
+    // `lb` when a row has at least 64 chunks; lanes below it take byte offset offA + 16*lane into
+    // the global tile, the others offB + 16*lane. These three numbers are wave-uniform and live in
+    // scalar registers (wide rows are the register-starved case). Narrow rows keep one per-lane
+    // offset per instruction in vector registers instead. A padding slot fetches the chunk that
+    // follows its row in memory and slots past the tile fetch further on; both are cut to the
+    // last valid chunk below and never read back from LDS.
+    const uint32_t pos_stride_k = (uint32_t)p.Hkv * DQK * 2;  // bytes between consecutive positions
+    const uint32_t pos_stride_v = (uint32_t)p.Hkv * DV * 2;
+    struct CopyPlan { uint32_t offA, offB; int lb; };
+    auto make_plan = [&](int instr, int cpr, uint32_t stride) {
+        CopyPlan c;
+        const int p0 = instr * 64, row0 = p0 / cpr, c0 = p0 - row0 * cpr;
+        if (cpr >= 64) {
+            c.lb = cpr - c0;  // first lane of the next row (>= 64: no row change inside)
+            c.offA = (uint32_t)row0 * stride + (uint32_t)c0 * 16u;
+            c.offB = (uint32_t)(row0 + 1) * stride - (uint32_t)c.lb * 16u;
+        } else {
+            const int pl = p0 + lane, row = pl / cpr;
+            c.lb = 64;
+            c.offA = (uint32_t)row * stride + (uint32_t)(pl - row * cpr) * 16u - lane16_of(lane);
+            c.offB = c.offA;
+        }
+        return c;
+    };
+    CopyPlan kplan[C::K_PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < C::K_PER_WAVE; ++u) kcode[u] = chunk_code(u * 4 + wave, C::K_INSTR, lane, N, C::KCPR);
-    int vcode[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
+    for (int u = 0; u < C::K_PER_WAVE; ++u) kplan[u] = make_plan(u * 4 + wave, C::KCPR, pos_stride_k);
+    CopyPlan vplan[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
 #pragma unroll
-    for (int u = 0; u < C::V_PER_WAVE; ++u) vcode[u] = chunk_code(u * 4 + wave, C::V_INSTR, lane, N, C::VCPR);
+    for (int u = 0; u < C::V_PER_WAVE; ++u) vplan[u] = make_plan(u * 4 + wave, C::VCPR, pos_stride_v);
+    const uint32_t lane16 = (uint32_t)lane * 16u;
 
-    const int64_t kv_pos_stride_k = (int64_t)p.Hkv * DQK * 2;  // bytes between consecutive positions
-    const int64_t kv_pos_stride_v = (int64_t)p.Hkv * DV * 2;
     const char *kbase = (const char *)p.k + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DQK * 2;
     const char *vbase = (const char *)p.v + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DV * 2;
 
     auto issue_tile = [&](int t, int stage) {
-        const int kt = t < nA ? t : wt0 + (t - nA);
-        const int64_t j0 = (int64_t)kt * N;
-        const int lim = (L - 1 - j0) < (N - 1) ? (int)(L - 1 - j0) : N - 1;  // last valid row in tile
-        const char *ksrc = kbase + j0 * kv_pos_stride_k;
-        char *kdst = smem + stage * C::STAGE;
+        const int64_t j0 = (int64_t)key_tile(t) * N;
+        // rows of the tile at or past the sequence end fetch from its last valid row instead:
+        // they are dead (j > i) and only have to be finite
+        const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
+        const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
+        char *kdst = smem + stage * C::STAGE + wave * 1024;
+        const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
 #pragma unroll
         for (int u = 0; u < C::K_PER_WAVE; ++u) {
-            if (kcode[u] >= 0) {
-                int row = kcode[u] & 0xff;
-                row = row < lim ? row : lim;  // rows past the sequence end repeat its last row
-                const int64_t off = (int64_t)row * kv_pos_stride_k + (kcode[u] >> 8) * 16;
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + off),
-                                                 (lds_void_ptr)(kdst + (u * 4 + wave) * 1024), 16, 0, 0);
+            if ((u + 1) * 4 <= C::K_INSTR || u * 4 + wave < C::K_INSTR) {  // wave-uniform
+                uint32_t off = (lane < kplan[u].lb ? kplan[u].offA : kplan[u].offB) + lane16;
+                off = off < kmax ? off : kmax;
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + off), (lds_void_ptr)(kdst + u * 4096), 16, 0, 0);
             }
         }
         if (!ALIAS) {
-            const char *vsrc = vbase + j0 * kv_pos_stride_v;
-            char *vdst = smem + stage * C::STAGE + C::KTILE;
+            const char *vsrc = vbase + j0 * (int64_t)pos_stride_v;
+            char *vdst = smem + stage * C::STAGE + C::KTILE + wave * 1024;
+            const uint32_t vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
 #pragma unroll
             for (int u = 0; u < C::V_PER_WAVE; ++u) {
-                if (vcode[u] >= 0) {
-                    int row = vcode[u] & 0xff;
-                    row = row < lim ? row : lim;
-                    const int64_t off = (int64_t)row * kv_pos_stride_v + (vcode[u] >> 8) * 16;
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(vsrc + off),
-                                                     (lds_void_ptr)(vdst + (u * 4 + wave) * 1024), 16, 0, 0);
+                if ((u + 1) * 4 <= C::V_INSTR || u * 4 + wave < C::V_INSTR) {
+                    uint32_t off = (lane < vplan[u].lb ? vplan[u].offA : vplan[u].offB) + lane16;
+                    off = off < vmax ? off : vmax;
+                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(vsrc + off), (lds_void_ptr)(vdst + u * 4096), 16, 0, 0);
                 }
             }
         }
@@ -230,8 +272,11 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[db][rb][e] = 0.f;
-    float m_run = LOZA_NEG_INF;  // running row maximum of scale*log2(e)*q.k
-    float l_run = 0.f;           // this lane's share of the running row sum
+    float m_ref = LOZA_NEG_INF;  // reference maximum of scale*log2(e)*q.k the exponentials are taken against
+    // This lane's share of the running row sums: of the exponentials as computed (-> log-sum-exp)
+    // and of the same values after rounding to bf16 (-> the normaliser of O, which is accumulated
+    // from the rounded values: the weights then sum to one exactly).
+    float l_run = 0.f, lr_run = 0.f;
 
     float *s_alpha = (float *)(smem + C::OFF_ALPHA);
     int *s_flag = (int *)(smem + C::OFF_FLAG);
@@ -239,36 +284,30 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     float *s_lpart = (float *)(smem + C::OFF_LPART);
     char *s_p = smem + C::OFF_P;
 
-    if (t_begin < t_end) issue_tile(t_begin, 0);
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int stage = (t - t_begin) & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile t has landed
-        lds_barrier();                     // ... and everyone's; the other stage and P are free
-        if (t + 1 < t_end) issue_tile(t + 1, stage ^ 1);
-
-        const int kt = t < nA ? t : wt0 + (t - nA);
-        const int j0 = kt * N;
-        const char *ktile = smem + stage * C::STAGE;
-        const char *vtile = ALIAS ? ktile : ktile + C::KTILE;
-
-        // ---- scores: S^T[32 keys of block wk][32 rows of block wr] ----------------------------
-        f32x16 s;
+    // ---- scores of one tile: S^T[32 keys of block wk][32 rows of block wr] ---------------------------
+    auto score_tile = [&](int stage, f32x16 &s) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[e] = 0.f;
-        {
-            const char *kp = ktile + (wk * 32 + ln) * C::KROW + lh * 16;
+        const char *kp = smem + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
+        constexpr int KS = DQK / 16, D = 4;
+        bf16x8 kf[D];
 #pragma unroll
-            for (int kk = 0; kk < DQK / 16; ++kk) {
-                const bf16x8 a = *(const bf16x8 *)(kp + kk * 32);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
-            }
+        for (int d = 0; d < D; ++d) kf[d] = *(const bf16x8 *)(kp + d * 32);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % D], qf[kk], s, 0, 0, 0);
+            if (kk + D < KS) kf[kk % D] = *(const bf16x8 *)(kp + (kk + D) * 32);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // ---- mask + online softmax of one tile; P (bf16), alpha and the rescale flag go to LDS ----------
+    auto softmax_tile = [&](f32x16 &s, const int j0, int pbuf, const float lazy) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[e] *= p.scale_log2;
-
-        // ---- mask, on tiles the pattern cuts ----------------------------------------------------
-        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));
+        // tiles the pattern cuts: causal diagonal, trailing edge of the window, end of the sink
+        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));  // j0 + N - 1 cannot overflow: j0 <= 0x3fffffff
         if (!interior) {
             const int jb = j0 + wk * 32 + 4 * lh;
 #pragma unroll
@@ -278,8 +317,6 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 s[e] = ok ? s[e] : LOZA_NEG_INF;
             }
         }
-
-        // ---- online softmax ----------------------------------------------------------------------
         float mx = s[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
@@ -290,39 +327,44 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 #pragma unroll
             for (int c = 0; c < KB; ++c) mx = fmaxf(mx, s_smax[c * M + wr * 32 + ln]);
         }
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
+        const bool up = mx > m_ref + lazy;  // also true on the first live tile (m_ref = -inf)
+        const float m_new = up ? mx : m_ref;
+        const float alpha = up ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;
+        m_ref = m_new;
+        const float m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;  // row with no live key so far
+        float psum = 0.f, rsum = 0.f;
+        uint32_t pk[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < 16; e += 2) {
             s[e] = __builtin_amdgcn_exp2f(s[e] - m_use);
-            psum += s[e];
+            s[e + 1] = __builtin_amdgcn_exp2f(s[e + 1] - m_use);
+            psum += s[e] + s[e + 1];
+            pk[e >> 1] = pack_bf16(s[e], s[e + 1]);
+            rsum += __builtin_bit_cast(float, pk[e >> 1] << 16) + __builtin_bit_cast(float, pk[e >> 1] & 0xffff0000u);
         }
         l_run = l_run * alpha + psum;
-        const bool rescale = __any(alpha != 1.0f);
+        lr_run = lr_run * alpha + rsum;
+        const bool rescale = __any(up);
         if (wk == 0) {
-            if (lane == 0) s_flag[wr] = rescale ? 1 : 0;
-            if (rescale && lh == 0) s_alpha[wr * 32 + ln] = alpha;
+            if (lane == 0) s_flag[pbuf * 4 + wr] = rescale ? 1 : 0;
+            if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = alpha;
         }
-        {
-            char *pp = s_p + (wr * 32 + ln) * C::PROW + (wk * 32 + 4 * lh) * 2;
+        char *pp = s_p + pbuf * C::PBYTES + (wr * 32 + ln) * C::PROW + (wk * 32 + 4 * lh) * 2;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                u32x2 w;
-                w[0] = pack_bf16(s[4 * qd + 0], s[4 * qd + 1]);
-                w[1] = pack_bf16(s[4 * qd + 2], s[4 * qd + 3]);
-                *(u32x2 *)(pp + qd * 16) = w;
-            }
+        for (int qd = 0; qd < 4; ++qd) {
+            u32x2 w;
+            w[0] = pk[2 * qd];
+            w[1] = pk[2 * qd + 1];
+            *(u32x2 *)(pp + qd * 16) = w;
         }
-        lds_barrier();
+    };
 
-        // ---- values: O^T[d_v slice of this wave][all rows] += V^T P^T ------------------------------
+    // ---- values of one tile: O^T[d_v slice of this wave][all rows] = alpha O^T + V^T P^T -------------
+    auto value_tile = [&](int stage, int pbuf) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            if (__builtin_amdgcn_readfirstlane(s_flag[rb])) {
-                const float a = s_alpha[rb * 32 + ln];
+            if (__builtin_amdgcn_readfirstlane(s_flag[pbuf * 4 + rb])) {
+                const float a = s_alpha[pbuf * M + rb * 32 + ln];
 #pragma unroll
                 for (int db = 0; db < C::DVB; ++db) {
                     // The accumulators live in the AGPR half of the register file; the empty asm
@@ -337,36 +379,98 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 }
             }
         }
-        {
-            const int s16 = lane & 15, g16 = (lane >> 4) & 1;
-            const char *vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
-            const char *pb = s_p + ln * C::PROW + lh * 16;
+        const char *vtile = smem + stage * C::STAGE + (ALIAS ? 0 : C::KTILE);
+        const int s16 = lane & 15, g16 = (lane >> 4) & 1;
+        const char *vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
+        const char *pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
+        constexpr int KS = N / 16;
+        // explicit software pipeline: the fragments of step (ks, db) + 1 are fetched from LDS while
+        // the RB matrix instructions of step (ks, db) run
+        auto load_v = [&](int step, s16x4 &lo, s16x4 &hi) {
+            const char *va = vp + (step / C::DVB) * 16 * C::VROW + (step % C::DVB) * 64;
+            lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+            hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
+        };
+        bf16x8 pf[2][RB];
+        s16x4 vlo[2], vhi[2];
 #pragma unroll
-            for (int ks = 0; ks < N / 16; ++ks) {
-                bf16x8 pf[RB];
+        for (int rb = 0; rb < RB; ++rb) pf[0][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW);
+        load_v(0, vlo[0], vhi[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) pf[rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW + ks * 32);
+        for (int step = 0; step < KS * C::DVB; ++step) {
+            const int ks = step / C::DVB, db = step % C::DVB;
+            if (step + 1 < KS * C::DVB) load_v(step + 1, vlo[(step + 1) & 1], vhi[(step + 1) & 1]);
+            if (db == 0 && ks + 1 < KS) {
 #pragma unroll
-                for (int db = 0; db < C::DVB; ++db) {
-                    const char *va = vp + ks * 16 * C::VROW + db * 64;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
-                    s16x8 a8;
-                    a8[0] = lo[0]; a8[1] = lo[1]; a8[2] = lo[2]; a8[3] = lo[3];
-                    a8[4] = hi[0]; a8[5] = hi[1]; a8[6] = hi[2]; a8[7] = hi[3];
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, a8);
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb], o[db][rb], 0, 0, 0);
-                }
+                for (int rb = 0; rb < RB; ++rb) pf[(ks + 1) & 1][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW + (ks + 1) * 32);
             }
+            s16x8 a8;
+            const s16x4 lo = vlo[step & 1], hi = vhi[step & 1];
+            a8[0] = lo[0]; a8[1] = lo[1]; a8[2] = lo[2]; a8[3] = lo[3];
+            a8[4] = hi[0]; a8[5] = hi[1]; a8[6] = hi[2]; a8[7] = hi[3];
+            const bf16x8 a = __builtin_bit_cast(bf16x8, a8);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[ks & 1][rb], o[db][rb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int nt = t_end - t_begin;
+    if (C::PIPE) {
+        // Software pipeline, one barrier per tile: while the value phase of tile u runs on the
+        // matrix cores, the scores of tile u + 1 are already in registers and their softmax runs on
+        // the vector ALUs; tile u + 2 is in flight from global memory.
+        if (nt > 0) {
+            issue_tile(t_begin, 0);
+            if (nt > 1) issue_tile(t_begin + 1, 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+            lds_barrier();
+            f32x16 s;
+            score_tile(0, s);
+            softmax_tile(s, key_tile(t_begin) * N, 0, 0.f);
+        }
+        int st_v = 0, st_k = 1, st_l = 2;  // stage of tile u (values), u + 1 (scores), u + 2 (load)
+        for (int u = 0; u < nt; ++u) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u + 1 has landed
+            lds_barrier();                     // ... everyone's; P of tile u is visible; stage st_l is free
+            if (u + 2 < nt) issue_tile(t_begin + u + 2, st_l);
+            {
+                // Past the last tile the score phase runs on a stale stage and its result is masked
+                // out as a whole (key index "infinity"), which leaves the softmax state untouched:
+                // one straight-line loop body instead of a peeled last iteration.
+                f32x16 s;
+                score_tile(st_k, s);
+                value_tile(st_v, u & 1);
+                softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
+                             u + 1 < LOZA_EXACT_MAX_TILES ? 0.f : LOZA_LAZY_RESCALE_LOG2);
+            }
+            const int tmp = st_v; st_v = st_k; st_k = st_l; st_l = tmp;
+        }
+    } else {
+        if (nt > 0) issue_tile(t_begin, 0);
+        for (int u = 0; u < nt; ++u) {
+            const int stage = u & 1;
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u has landed
+            lds_barrier();                     // ... and everyone's; the other stage and P are free
+            if (u + 1 < nt) issue_tile(t_begin + u + 1, stage ^ 1);
+            f32x16 s;
+            score_tile(stage, s);
+            softmax_tile(s, key_tile(t_begin + u) * N, 0, u < LOZA_EXACT_MAX_TILES ? 0.f : LOZA_LAZY_RESCALE_LOG2);
+            lds_barrier();
+            value_tile(stage, 0);
         }
     }
 
     // ---- epilogue ----------------------------------------------------------------------------------
     {
         const float l_lane = l_run + xor32(l_run);
-        if (lh == 0) s_lpart[wk * M + wr * 32 + ln] = l_lane;
+        const float lr_lane = lr_run + xor32(lr_run);
+        if (lh == 0) {
+            s_lpart[wk * M + wr * 32 + ln] = l_lane;
+            s_lpart[(KB + wk) * M + wr * 32 + ln] = lr_lane;
+        }
     }
     lds_barrier();
     float l_tot_mine = 0.f;
@@ -374,19 +478,19 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     for (int c = 0; c < KB; ++c) l_tot_mine += s_lpart[c * M + wr * 32 + ln];
 
     if (!DECODE) {
-        // lse = ln(sum_j exp(scale q.k_j)) = (m + log2 l) * ln 2
+        // lse = ln(sum_j exp(scale q.k_j)) = (m_ref + log2 l) * ln 2
         if (wk == 0 && lh == 0 && my_row < R) {
             const int hh = (int)(my_row - (int64_t)i_row * G);
             p.lse[((int64_t)b * p.Hq + (int64_t)g * G + hh) * p.S + i_row] =
-                (m_run + __builtin_amdgcn_logf(l_tot_mine)) * 0.69314718055994530942f;
+                (m_ref + __builtin_amdgcn_logf(l_tot_mine)) * 0.69314718055994530942f;
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             const int64_t row = r0 + rb * 32 + ln;
-            float l_tot = 0.f;
+            float lr_tot = 0.f;
 #pragma unroll
-            for (int c = 0; c < KB; ++c) l_tot += s_lpart[c * M + rb * 32 + ln];
-            const float inv = 1.0f / l_tot;
+            for (int c = 0; c < KB; ++c) lr_tot += s_lpart[(KB + c) * M + rb * 32 + ln];
+            const float inv = 1.0f / lr_tot;
             if (row < R) {
                 const int64_t i = row / G;
                 const int hh = (int)(row - i * G);
@@ -403,11 +507,15 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
         }
     } else {
-        // partial result of this key split: unnormalised O (relative to m), m, l
+        // partial result of this key split: unnormalised O (relative to m_ref), m_ref, l, rounded l
         if (wk == 0 && lh == 0 && my_row < R) {
             const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + my_row;
-            p.part_ml[(h * p.n_splits + split) * 2 + 0] = m_run;
-            p.part_ml[(h * p.n_splits + split) * 2 + 1] = l_tot_mine;
+            float lr_tot_mine = 0.f;
+#pragma unroll
+            for (int c = 0; c < KB; ++c) lr_tot_mine += s_lpart[(KB + c) * M + wr * 32 + ln];
+            p.part_ml[(h * p.n_splits + split) * 4 + 0] = m_ref;
+            p.part_ml[(h * p.n_splits + split) * 4 + 1] = l_tot_mine;
+            p.part_ml[(h * p.n_splits + split) * 4 + 2] = lr_tot_mine;
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
@@ -431,8 +539,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     }
 }
 
-// Merge of the key splits of one decode query (log-sum-exp rule, fixed split order):
-//   m* = max_s m_s ;  w_s = 2^(m_s - m*) ;  out = sum_s w_s O_s / sum_s w_s l_s ;
+// Merge of the key splits of one decode query (log-sum-exp rule, fixed split order). Each split s
+// left O_s (unnormalised, relative to its reference m_s), the sum l_s of its exponentials and the
+// sum r_s of the same values as rounded to bf16 (what O_s was accumulated from):
+//   m* = max_s m_s ;  w_s = 2^(m_s - m*) ;  out = sum_s w_s O_s / sum_s w_s r_s ;
 //   lse = (m* + log2 sum_s w_s l_s) ln 2.
 template <int DV>
 __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const float *__restrict__ part_o,
@@ -441,9 +551,9 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const float *_
                                                                    float *__restrict__ lse, int n_splits)
 {
     const int64_t h = blockIdx.x;  // flat (b, query head)
-    const float *ml = part_ml + h * n_splits * 2;
+    const float *ml = part_ml + h * n_splits * 4;
     float m_star = LOZA_NEG_INF;
-    for (int s = 0; s < n_splits; ++s) m_star = fmaxf(m_star, ml[2 * s]);
+    for (int s = 0; s < n_splits; ++s) m_star = fmaxf(m_star, ml[4 * s]);
     const int c = threadIdx.x * 4;
     if (m_star == LOZA_NEG_INF) {  // no live key at all (empty cache)
         u32x2 z; z[0] = 0; z[1] = 0;
@@ -451,15 +561,16 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const float *_
         if (threadIdx.x == 0) lse[h] = LOZA_NEG_INF;
         return;
     }
-    float den = 0.f;
+    float den = 0.f, den_r = 0.f;
     float4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < n_splits; ++s) {
-        const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m_star);
-        den += w * ml[2 * s + 1];
+        const float w = __builtin_amdgcn_exp2f(ml[4 * s] - m_star);
+        den += w * ml[4 * s + 1];
+        den_r += w * ml[4 * s + 2];
         const float4 v = *(const float4 *)(part_o + (h * n_splits + s) * DV + c);
         acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
     }
-    const float inv = 1.0f / den;
+    const float inv = 1.0f / den_r;
     u32x2 w2;
     w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
     w2[1] = pack_bf16(acc.z * inv, acc.w * inv);

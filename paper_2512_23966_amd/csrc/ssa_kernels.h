@@ -15,7 +15,7 @@ struct FwdParams {
     uint16_t *out;
     float *lse;
     float *part_o;   // decode: [B, Hq, n_splits, d_v] unnormalised partial outputs
-    float *part_ml;  // decode: [B, Hq, n_splits, 2]   running max (log2 domain), partial sum
+    float *part_ml;  // decode: [B, Hq, n_splits, 4]   reference max (log2 domain), sum, rounded sum, pad
     const int32_t *seqlens;
     int B, Hq, Hkv, G;
     int64_t S;
