@@ -47,6 +47,14 @@ int decode_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t
     return (int)n;
 }
 
+void set_rescale_policy(loza::FwdParams &p)
+{
+    p.exact_tiles = 8;
+    p.lazy_log2 = 8.0f;
+    if (const char *e = getenv("LOZA_EXACT_TILES")) p.exact_tiles = atoi(e);
+    if (const char *e = getenv("LOZA_LAZY_LOG2")) p.lazy_log2 = (float)atof(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -109,6 +117,7 @@ int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, flo
     p.n_sink = clamp_to(n_sink, S); p.window = clamp_to(window, S);
     p.scale_log2 = scale * 1.44269504088896340736f;
     p.row_tiles = (int)row_tiles; p.n_splits = 1;
+    set_rescale_policy(p);
     return loza::launch_prefill_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 
@@ -179,6 +188,7 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
     p.n_sink = clamp_to(n_sink, S_max); p.window = clamp_to(window, S_max);
     p.scale_log2 = scale * 1.44269504088896340736f;
     p.row_tiles = (int)row_tiles; p.n_splits = n_splits;
+    set_rescale_policy(p);
     return loza::launch_decode_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 

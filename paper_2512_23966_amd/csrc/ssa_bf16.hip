@@ -23,6 +23,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
+#include "score_asm.h"
 #include "ssa_kernels.h"
 
 namespace loza {
@@ -56,13 +59,30 @@ static __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// max(x, value of x in the lane of the other wavefront half (lane ^ 32)), without touching LDS.
+static __device__ __forceinline__ float max_with_other_half(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    // v_permlane32_swap exchanges one half of its first operand with the opposite half of the
+    // second; fed with two copies of x, one result holds the low half's values in both halves and
+    // the other the high half's, so their maximum is the wanted value in every lane
+    // (the copy and both results go through empty asm statements: the optimiser otherwise folds
+    // the maximum of the two results of a swap into the first result alone)
+    uint32_t u2 = u;
+    asm volatile("" : "+v"(u2));
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u2, false, false);
+    uint32_t r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    return fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+}
+
 static __device__ __forceinline__ float xor32(float x)
 {
     // value held by the lane in the other half of the wavefront (lane ^ 32)
     return __shfl_xor(x, 32, 64);
 }
 
-template <int DQK, int DV, int RB, int KB, bool ALIAS>
+template <int DQK, int DV, int RB, int KB, bool ALIAS, bool PRECISE = false>
 struct TileCfg {
     static constexpr int M = 32 * RB;            // query rows per workgroup
     static constexpr int N = 32 * KB;            // keys per tile
@@ -89,7 +109,9 @@ struct TileCfg {
     // KB == 2 (decode): two stages, one P buffer
     static constexpr bool PIPE = (KB == 1);
     static constexpr int NSTAGE = PIPE ? 3 : 2;
-    static constexpr int NPBUF = PIPE ? 2 : 1;
+    // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer
+    static constexpr int NPBUF = (PIPE ? 2 : 1) * (PRECISE ? 2 : 1);
+    static constexpr int PLO = PIPE ? 2 : 1;         // index offset of the low-term buffers
     static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
     static constexpr int PBYTES = M * PROW;
     static constexpr int OFF_P = NSTAGE * STAGE;
@@ -121,10 +143,10 @@ static __device__ __forceinline__ uint32_t chunk_offset(int instr, int lane, int
 #define LOZA_LAZY_RESCALE_LOG2 8.0f
 #define LOZA_EXACT_MAX_TILES 8
 
-template <int DQK, int DV, int RB, int KB, bool ALIAS, bool DECODE>
+template <int DQK, int DV, int RB, int KB, bool ALIAS, bool DECODE, bool PRECISE = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
-    using C = TileCfg<DQK, DV, RB, KB, ALIAS>;
+    using C = TileCfg<DQK, DV, RB, KB, ALIAS, PRECISE>;
     constexpr int M = C::M, N = C::N;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -136,7 +158,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     int id = blockIdx.x;
     int split = 0;
     if (DECODE) { split = id % p.n_splits; id /= p.n_splits; }
-    const int rt = p.row_tiles - 1 - (id % p.row_tiles);  // heaviest (latest) row tiles first
+    const int rt = p.rt_begin + p.row_tiles - 1 - (id % p.row_tiles);  // heaviest (latest) row tiles first
     id /= p.row_tiles;
     const int g = id % p.Hkv;
     const int b = id / p.Hkv;
@@ -285,85 +307,111 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     char *s_p = smem + C::OFF_P;
 
     // ---- scores of one tile: S^T[32 keys of block wk][32 rows of block wr] ---------------------------
+    // One inline-asm statement (score_asm.h): key fragment kk + DEPTH is fetched from LDS while
+    // fragment kk feeds the matrix core, with the exact lgkmcnt each step needs. The accumulator is
+    // in VGPRs (the AGPR half of the register file is full of O).
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
     auto score_tile = [&](int stage, f32x16 &s) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = 0.f;
-        const char *kp = smem + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
-        constexpr int KS = DQK / 16, D = 4;
-        bf16x8 kf[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) kf[d] = *(const bf16x8 *)(kp + d * 32);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % D], qf[kk], s, 0, 0, 0);
-            if (kk + D < KS) kf[kk % D] = *(const bf16x8 *)(kp + (kk + D) * 32);
-            __builtin_amdgcn_sched_barrier(0);
+        const uint32_t kaddr = smem_lds + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
+        static_assert(DQK == 576 || DQK == 128, "add a LOZA_SCORE_PHASE for this d_qk");
+        if constexpr (DQK == 576) {
+            bf16x8 kf[LOZA_SCORE_DEPTH_576];
+            LOZA_SCORE_PHASE_576(s, kf, kaddr, qf);
+        } else {
+            bf16x8 kf[LOZA_SCORE_DEPTH_128];
+            LOZA_SCORE_PHASE_128(s, kf, kaddr, qf);
         }
     };
 
-    // ---- mask + online softmax of one tile; P (bf16), alpha and the rescale flag go to LDS ----------
-    auto softmax_tile = [&](f32x16 &s, const int j0, int pbuf, const float lazy) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] *= p.scale_log2;
+    // ---- mask + online softmax of one tile, in three parts so that the value phase can run them
+    //      between its matrix instructions; P (bf16), alpha and the rescale flag go to LDS -------------
+    float sm_m_use = 0.f, sm_alpha = 1.f, sm_psum = 0.f, sm_rsum = 0.f;
+    bool sm_up = false;
+    uint32_t sm_pk[8];
+    uint32_t sm_pk_lo[PRECISE ? 8 : 1];
+    auto sm_begin = [&](f32x16 &s, const int j0, const float lazy) {
         // tiles the pattern cuts: causal diagonal, trailing edge of the window, end of the sink
-        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));  // j0 + N - 1 cannot overflow: j0 <= 0x3fffffff
+        // (j0 + N - 1 cannot overflow: j0 <= 0x3fffffff, the "no such tile" marker, masks everything)
+        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));
         if (!interior) {
             const int jb = j0 + wk * 32 + 4 * lh;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int j = jb + 8 * (e >> 2) + (e & 3);
-                const bool ok = (j <= i_row) && (j < n_sink || i_row - j < window);
+                const bool ok = (j <= i_row) & ((j < n_sink) | (i_row - j < window));
                 s[e] = ok ? s[e] : LOZA_NEG_INF;
             }
         }
         float mx = s[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
-        mx = fmaxf(mx, xor32(mx));
+        mx = max_with_other_half(mx);
+        mx *= p.scale_log2;  // scale > 0: the maximum of the scaled scores
         if (KB > 1) {
             if (lh == 0) s_smax[wk * M + wr * 32 + ln] = mx;
             lds_barrier();
 #pragma unroll
             for (int c = 0; c < KB; ++c) mx = fmaxf(mx, s_smax[c * M + wr * 32 + ln]);
         }
-        const bool up = mx > m_ref + lazy;  // also true on the first live tile (m_ref = -inf)
-        const float m_new = up ? mx : m_ref;
-        const float alpha = up ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;
+        sm_up = mx > m_ref + lazy;  // also true on the first live tile (m_ref = -inf)
+        const float m_new = sm_up ? mx : m_ref;
+        sm_alpha = sm_up ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;
         m_ref = m_new;
-        const float m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;  // row with no live key so far
-        float psum = 0.f, rsum = 0.f;
-        uint32_t pk[8];
+        sm_m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;  // row with no live key so far
+        sm_psum = 0.f;
+        sm_rsum = 0.f;
+    };
+    auto sm_elems = [&](f32x16 &s, const int e0, const int e1) {
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-            s[e] = __builtin_amdgcn_exp2f(s[e] - m_use);
-            s[e + 1] = __builtin_amdgcn_exp2f(s[e + 1] - m_use);
-            psum += s[e] + s[e + 1];
-            pk[e >> 1] = pack_bf16(s[e], s[e + 1]);
-            rsum += __builtin_bit_cast(float, pk[e >> 1] << 16) + __builtin_bit_cast(float, pk[e >> 1] & 0xffff0000u);
+        for (int e = e0; e < e1; e += 2) {
+            // exp2(scale*log2(e)*s - m): a dead key (s = -inf) gives exactly 0
+            s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], p.scale_log2, -sm_m_use));
+            s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
+            sm_psum += s[e] + s[e + 1];
+            sm_pk[e >> 1] = pack_bf16(s[e], s[e + 1]);
+            const float h0 = __builtin_bit_cast(float, sm_pk[e >> 1] << 16), h1 = __builtin_bit_cast(float, sm_pk[e >> 1] & 0xffff0000u);
+            sm_rsum += h0 + h1;
+            if (PRECISE) {
+                // second bf16 term of each weight: what the first rounding lost
+                sm_pk_lo[e >> 1] = pack_bf16(s[e] - h0, s[e + 1] - h1);
+                sm_rsum += __builtin_bit_cast(float, sm_pk_lo[e >> 1] << 16) + __builtin_bit_cast(float, sm_pk_lo[e >> 1] & 0xffff0000u);
+            }
         }
-        l_run = l_run * alpha + psum;
-        lr_run = lr_run * alpha + rsum;
-        const bool rescale = __any(up);
+    };
+    auto sm_end = [&](const int pbuf) {
+        l_run = l_run * sm_alpha + sm_psum;
+        lr_run = lr_run * sm_alpha + sm_rsum;
+        const bool rescale = __any(sm_up);
         if (wk == 0) {
             if (lane == 0) s_flag[pbuf * 4 + wr] = rescale ? 1 : 0;
-            if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = alpha;
+            if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = sm_alpha;
         }
         char *pp = s_p + pbuf * C::PBYTES + (wr * 32 + ln) * C::PROW + (wk * 32 + 4 * lh) * 2;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             u32x2 w;
-            w[0] = pk[2 * qd];
-            w[1] = pk[2 * qd + 1];
+            w[0] = sm_pk[2 * qd];
+            w[1] = sm_pk[2 * qd + 1];
             *(u32x2 *)(pp + qd * 16) = w;
+            if (PRECISE) {
+                w[0] = sm_pk_lo[2 * qd];
+                w[1] = sm_pk_lo[2 * qd + 1];
+                *(u32x2 *)(pp + C::PLO * C::PBYTES + qd * 16) = w;
+            }
         }
     };
+    auto softmax_tile = [&](f32x16 &s, const int j0, const int pbuf, const float lazy) {
+        sm_begin(s, j0, lazy);
+        sm_elems(s, 0, 16);
+        sm_end(pbuf);
+    };
 
-    // ---- values of one tile: O^T[d_v slice of this wave][all rows] = alpha O^T + V^T P^T -------------
-    auto value_tile = [&](int stage, int pbuf) {
+    // ---- accumulator rescale of one tile (rare after the first tiles) -----------------------------------
+    auto rescale_tile = [&](const int pbuf) {
+        const u32x4 flags = *(const u32x4 *)(s_flag + pbuf * 4);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            if (__builtin_amdgcn_readfirstlane(s_flag[pbuf * 4 + rb])) {
+            if (__builtin_amdgcn_readfirstlane(flags[rb])) {
                 const float a = s_alpha[pbuf * M + rb * 32 + ln];
 #pragma unroll
                 for (int db = 0; db < C::DVB; ++db) {
@@ -379,13 +427,21 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 }
             }
         }
+    };
+
+    // ---- values of one tile: O^T[d_v slice of this wave][all rows] += V^T P^T -------------------------
+    // Explicit software pipeline over the (key step, column block) pairs: the fragments of the next
+    // pair are fetched from LDS while the RB matrix instructions of this pair run. With WITH_SOFTMAX
+    // the softmax of the NEXT tile (scores in `s`) is cut into pieces that are issued between the
+    // matrix instructions, so that the vector ALUs work in the shadow of the matrix cores.
+    auto value_tile = [&](const int stage, const int pbuf, auto with_softmax, f32x16 &s, const int j0_next,
+                          const int pbuf_next, const float lazy) {
+        constexpr bool WITH_SOFTMAX = decltype(with_softmax)::value;
         const char *vtile = smem + stage * C::STAGE + (ALIAS ? 0 : C::KTILE);
         const int s16 = lane & 15, g16 = (lane >> 4) & 1;
         const char *vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
         const char *pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
-        constexpr int KS = N / 16;
-        // explicit software pipeline: the fragments of step (ks, db) + 1 are fetched from LDS while
-        // the RB matrix instructions of step (ks, db) run
+        constexpr int KS = N / 16, NSTEP = KS * C::DVB;
         auto load_v = [&](int step, s16x4 &lo, s16x4 &hi) {
             const char *va = vp + (step / C::DVB) * 16 * C::VROW + (step % C::DVB) * 64;
             lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
@@ -393,14 +449,15 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         };
         bf16x8 pf[2][RB];
         s16x4 vlo[2], vhi[2];
+        const char *pb_lo = pb + C::PLO * C::PBYTES;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) pf[0][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW);
         load_v(0, vlo[0], vhi[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int step = 0; step < KS * C::DVB; ++step) {
+        for (int step = 0; step < NSTEP; ++step) {
             const int ks = step / C::DVB, db = step % C::DVB;
-            if (step + 1 < KS * C::DVB) load_v(step + 1, vlo[(step + 1) & 1], vhi[(step + 1) & 1]);
+            if (step + 1 < NSTEP) load_v(step + 1, vlo[(step + 1) & 1], vhi[(step + 1) & 1]);
             if (db == 0 && ks + 1 < KS) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) pf[(ks + 1) & 1][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW + (ks + 1) * 32);
@@ -413,21 +470,45 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[ks & 1][rb], o[db][rb], 0, 0, 0);
+            if (PRECISE) {
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    const bf16x8 pl = *(const bf16x8 *)(pb_lo + rb * 32 * C::PROW + ks * 32);
+                    o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, o[db][rb], 0, 0, 0);
+                }
+            }
+            if (WITH_SOFTMAX) {
+                // piece `step` of the next tile's softmax: statistics first, then the 16 scores of
+                // this lane spread over the remaining steps, the LDS hand-over last
+                if (step == 0) sm_begin(s, j0_next, lazy);
+                if (NSTEP >= 4) {
+                    constexpr int PER = (16 / (NSTEP > 2 ? NSTEP - 2 : 1) + 1) & ~1;  // even number of scores per step
+                    if (step >= 1 && step <= NSTEP - 2) {
+                        const int e0 = (step - 1) * PER, e1 = e0 + PER < 16 ? e0 + PER : 16;
+                        if (e0 < 16) sm_elems(s, e0, step == NSTEP - 2 ? 16 : e1);
+                    }
+                } else if (step == NSTEP - 1) {
+                    sm_elems(s, 0, 16);
+                }
+                if (step == NSTEP - 1) sm_end(pbuf_next);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    using yes_t = std::true_type;
+    using no_t = std::false_type;
 
     const int nt = t_end - t_begin;
     if (C::PIPE) {
         // Software pipeline, one barrier per tile: while the value phase of tile u runs on the
         // matrix cores, the scores of tile u + 1 are already in registers and their softmax runs on
         // the vector ALUs; tile u + 2 is in flight from global memory.
+        f32x16 s;
         if (nt > 0) {
             issue_tile(t_begin, 0);
             if (nt > 1) issue_tile(t_begin + 1, 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
             lds_barrier();
-            f32x16 s;
             score_tile(0, s);
             softmax_tile(s, key_tile(t_begin) * N, 0, 0.f);
         }
@@ -436,30 +517,28 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u + 1 has landed
             lds_barrier();                     // ... everyone's; P of tile u is visible; stage st_l is free
             if (u + 2 < nt) issue_tile(t_begin + u + 2, st_l);
-            {
-                // Past the last tile the score phase runs on a stale stage and its result is masked
-                // out as a whole (key index "infinity"), which leaves the softmax state untouched:
-                // one straight-line loop body instead of a peeled last iteration.
-                f32x16 s;
-                score_tile(st_k, s);
-                value_tile(st_v, u & 1);
-                softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
-                             u + 1 < LOZA_EXACT_MAX_TILES ? 0.f : LOZA_LAZY_RESCALE_LOG2);
-            }
+            // Past the last tile the score phase runs on a stale stage and its result is masked out
+            // as a whole (key index "infinity"), which leaves the softmax state untouched: one
+            // straight-line loop body instead of a peeled last iteration.
+            score_tile(st_k, s);
+            rescale_tile(u & 1);
+            value_tile(st_v, u & 1, yes_t{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
+                       u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
             const int tmp = st_v; st_v = st_k; st_k = st_l; st_l = tmp;
         }
     } else {
+        f32x16 s;
         if (nt > 0) issue_tile(t_begin, 0);
         for (int u = 0; u < nt; ++u) {
             const int stage = u & 1;
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u has landed
             lds_barrier();                     // ... and everyone's; the other stage and P are free
             if (u + 1 < nt) issue_tile(t_begin + u + 1, stage ^ 1);
-            f32x16 s;
             score_tile(stage, s);
-            softmax_tile(s, key_tile(t_begin + u) * N, 0, u < LOZA_EXACT_MAX_TILES ? 0.f : LOZA_LAZY_RESCALE_LOG2);
+            softmax_tile(s, key_tile(t_begin + u) * N, 0, u < p.exact_tiles ? 0.f : p.lazy_log2);
             lds_barrier();
-            value_tile(stage, 0);
+            rescale_tile(0);
+            value_tile(stage, 0, no_t{}, s, 0, 0, 0.f);
         }
     }
 
@@ -579,16 +658,36 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const float *_
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Positions below this take the two-term-P variant of the prefill kernel: with so few live keys
+// the output is as large as single value rows, and the bf16 rounding of P would be a visible share
+// of the error budget there. Beyond it every output averages enough keys for that to vanish.
+constexpr int kPrecisePositions = 128;
+
+template <int DQK, int DV, bool ALIAS, bool PRECISE>
+static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
+{
+    if (rt_count <= 0) return hipSuccess;
+    using C = TileCfg<DQK, DV, 4, 1, ALIAS, PRECISE>;
+    auto kern = ssa_fwd_kernel<DQK, DV, 4, 1, ALIAS, false, PRECISE>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    p.rt_begin = rt_begin;
+    p.row_tiles = rt_count;
+    const int64_t blocks = (int64_t)rt_count * p.Hkv * p.B;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
+    return hipGetLastError();
+}
+
 template <int DQK, int DV, bool ALIAS>
 static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
 {
-    using C = TileCfg<DQK, DV, 4, 1, ALIAS>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 4, 1, ALIAS, false>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
+    int n_prec = (int)((prec_rows + 127) / 128);
+    if (n_prec > p.row_tiles) n_prec = p.row_tiles;
+    // the long tiles first: the short precise ones fill the tail
+    hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false>(p, n_prec, p.row_tiles - n_prec, stream);
     if (e != hipSuccess) return e;
-    const int64_t blocks = (int64_t)p.row_tiles * p.Hkv * p.B;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
-    return hipGetLastError();
+    return launch_prefill_part<DQK, DV, ALIAS, true>(p, 0, n_prec, stream);
 }
 
 template <int DQK, int DV, bool ALIAS>

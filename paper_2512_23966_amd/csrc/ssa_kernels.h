@@ -21,8 +21,11 @@ struct FwdParams {
     int64_t S;
     int n_sink, window;
     float scale_log2;  // scale * log2(e)
-    int row_tiles;     // workgroup tiles per (batch, kv head)
+    int row_tiles;     // workgroup tiles per (batch, kv head) in this launch
+    int rt_begin;      // first of them
     int n_splits;      // decode only
+    int exact_tiles;   // tiles over which the reference maximum is the exact running maximum
+    float lazy_log2;   // afterwards it moves only when exceeded by this much (log2 units)
 };
 
 bool bf16_shape_supported(int d_qk, int d_v, bool alias);
