@@ -7,12 +7,14 @@ fallback: if the shared library is missing, importing a symbol from it raises.
 from __future__ import annotations
 
 import ctypes
+import os
 from pathlib import Path
 
 import torch
 
 _PKG = Path(__file__).resolve().parent
-LIB_PATH = _PKG / "libloza_ssa.so"
+# LOZA_SSA_LIB names another build of the same library (kernel experiments); default: the in-tree one
+LIB_PATH = Path(os.environ["LOZA_SSA_LIB"]) if os.environ.get("LOZA_SSA_LIB") else _PKG / "libloza_ssa.so"
 _lib = None
 
 LOZA_OK = 0

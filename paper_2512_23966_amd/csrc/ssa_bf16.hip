@@ -256,6 +256,11 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const char *kbase = (const char *)p.k + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DQK * 2;
     const char *vbase = (const char *)p.v + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DV * 2;
 
+    // per-lane byte offsets of this wave's copy instructions (before the cut to the last valid chunk)
+    uint32_t kvoff[C::K_PER_WAVE];
+#pragma unroll
+    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = (lane < kplan[u].lb ? kplan[u].offA : kplan[u].offB) + lane16;
+
     auto issue_tile = [&](int t, int stage) {
         const int64_t j0 = (int64_t)key_tile(t) * N;
         // rows of the tile at or past the sequence end fetch from its last valid row instead:
@@ -311,6 +316,28 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // fragment kk feeds the matrix core, with the exact lgkmcnt each step needs. The accumulator is
     // in VGPRs (the AGPR half of the register file is full of O).
     const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+    // The same with the copy of key tile `t_copy` into stage `stage_copy` woven in (wide rows only):
+    // the copy instructions issue between matrix instructions instead of ahead of them.
+    auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy) {
+        if constexpr (DQK == 576 && ALIAS && C::PIPE) {
+            const uint32_t kaddr = smem_lds + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
+            const int64_t j0 = (int64_t)key_tile(t_copy) * N;
+            const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
+            const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
+            const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
+            const uint32_t m0base = smem_lds + stage_copy * C::STAGE + wave * 1024;
+            static_assert(LOZA_SCORE_COPIES_576 * 4 <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576 + 1, "copy plan");
+            bf16x8 kf[LOZA_SCORE_DEPTH_576];
+            uint32_t tmp;
+            LOZA_SCORE_PHASE_576_COPY(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
+            // the instruction past the woven ones exists for the first waves only
+            if (LOZA_SCORE_COPIES_576 < C::K_PER_WAVE && LOZA_SCORE_COPIES_576 * 4 + wave < C::K_INSTR) {
+                const uint32_t off = kvoff[C::K_PER_WAVE - 1] < kmax ? kvoff[C::K_PER_WAVE - 1] : kmax;
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + off),
+                                                 (lds_void_ptr)(smem + stage_copy * C::STAGE + wave * 1024 + LOZA_SCORE_COPIES_576 * 4096), 16, 0, 0);
+            }
+        }
+    };
     auto score_tile = [&](int stage, f32x16 &s) {
         const uint32_t kaddr = smem_lds + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
         static_assert(DQK == 576 || DQK == 128, "add a LOZA_SCORE_PHASE for this d_qk");
@@ -407,8 +434,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
 
     // ---- accumulator rescale of one tile (rare after the first tiles) -----------------------------------
-    auto rescale_tile = [&](const int pbuf) {
-        const u32x4 flags = *(const u32x4 *)(s_flag + pbuf * 4);
+    auto rescale_flags = [&](const int pbuf) { return *(const u32x4 *)(s_flag + pbuf * 4); };
+    auto rescale_tile = [&](const int pbuf, const u32x4 flags) {
+        // one test covers the common case that no row block of the tile moved its reference
+        if (__builtin_amdgcn_readfirstlane(flags[0] | flags[1] | flags[2] | flags[3]) == 0) return;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             if (__builtin_amdgcn_readfirstlane(flags[rb])) {
@@ -448,22 +477,23 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
         };
         bf16x8 pf[2][RB];
-        s16x4 vlo[2], vhi[2];
+        s16x4 vlo[3], vhi[3];  // value fragments: two steps of look-ahead
         const char *pb_lo = pb + C::PLO * C::PBYTES;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) pf[0][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW);
         load_v(0, vlo[0], vhi[0]);
+        if (NSTEP > 1) load_v(1, vlo[1], vhi[1]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             const int ks = step / C::DVB, db = step % C::DVB;
-            if (step + 1 < NSTEP) load_v(step + 1, vlo[(step + 1) & 1], vhi[(step + 1) & 1]);
+            if (step + 2 < NSTEP) load_v(step + 2, vlo[(step + 2) % 3], vhi[(step + 2) % 3]);
             if (db == 0 && ks + 1 < KS) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) pf[(ks + 1) & 1][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW + (ks + 1) * 32);
             }
             s16x8 a8;
-            const s16x4 lo = vlo[step & 1], hi = vhi[step & 1];
+            const s16x4 lo = vlo[step % 3], hi = vhi[step % 3];
             a8[0] = lo[0]; a8[1] = lo[1]; a8[2] = lo[2]; a8[3] = lo[3];
             a8[4] = hi[0]; a8[5] = hi[1]; a8[6] = hi[2]; a8[7] = hi[3];
             const bf16x8 a = __builtin_bit_cast(bf16x8, a8);
@@ -480,12 +510,22 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             if (WITH_SOFTMAX) {
                 // piece `step` of the next tile's softmax: statistics first, then the 16 scores of
                 // this lane spread over the remaining steps, the LDS hand-over last
-                if (step == 0) sm_begin(s, j0_next, lazy);
+                // (the empty asm statements anchor each piece in its step: without them the
+                // optimiser sinks all of this arithmetic below the last matrix instruction)
+                if (step == 0) {
+                    sm_begin(s, j0_next, lazy);
+                    asm volatile("" : "+v"(s), "+v"(sm_m_use), "+v"(sm_alpha));
+                }
                 if (NSTEP >= 4) {
                     constexpr int PER = (16 / (NSTEP > 2 ? NSTEP - 2 : 1) + 1) & ~1;  // even number of scores per step
                     if (step >= 1 && step <= NSTEP - 2) {
-                        const int e0 = (step - 1) * PER, e1 = e0 + PER < 16 ? e0 + PER : 16;
-                        if (e0 < 16) sm_elems(s, e0, step == NSTEP - 2 ? 16 : e1);
+                        const int e0 = (step - 1) * PER, e1 = step == NSTEP - 2 ? 16 : (e0 + PER < 16 ? e0 + PER : 16);
+                        if (e0 < 16) {
+                            sm_elems(s, e0, e1);
+#pragma unroll
+                            for (int e = e0; e < e1; e += 2) asm volatile("" : "+v"(sm_pk[e >> 1]));
+                            asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum));
+                        }
                     }
                 } else if (step == NSTEP - 1) {
                     sm_elems(s, 0, 16);
@@ -516,12 +556,15 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         for (int u = 0; u < nt; ++u) {
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u + 1 has landed
             lds_barrier();                     // ... everyone's; P of tile u is visible; stage st_l is free
-            if (u + 2 < nt) issue_tile(t_begin + u + 2, st_l);
+            constexpr bool WEAVE = (DQK == 576 && ALIAS && C::PIPE);  // copy instructions inside the score phase
+            if (!WEAVE && u + 2 < nt) issue_tile(t_begin + u + 2, st_l);
             // Past the last tile the score phase runs on a stale stage and its result is masked out
             // as a whole (key index "infinity"), which leaves the softmax state untouched: one
             // straight-line loop body instead of a peeled last iteration.
-            score_tile(st_k, s);
-            rescale_tile(u & 1);
+            const u32x4 flags = rescale_flags(u & 1);  // requested now, used after the score phase
+            if (WEAVE && u + 2 < nt) score_tile_copy(st_k, s, t_begin + u + 2, st_l);
+            else score_tile(st_k, s);
+            rescale_tile(u & 1, flags);
             value_tile(st_v, u & 1, yes_t{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
                        u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
             const int tmp = st_v; st_v = st_k; st_k = st_l; st_l = tmp;
@@ -537,7 +580,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             score_tile(stage, s);
             softmax_tile(s, key_tile(t_begin + u) * N, 0, u < p.exact_tiles ? 0.f : p.lazy_log2);
             lds_barrier();
-            rescale_tile(0);
+            rescale_tile(0, rescale_flags(0));
             value_tile(stage, 0, no_t{}, s, 0, 0, 0.f);
         }
     }
