@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     bool sm_up = false;
     uint32_t sm_pk[8];
     uint32_t sm_pk_lo[PRECISE ? 8 : 1];
-    auto sm_begin = [&](f32x16 &s, const int j0, const float lazy) {
+    auto sm_mask = [&](f32x16 &s, const int j0) {
         // tiles the pattern cuts: causal diagonal, trailing edge of the window, end of the sink
         // (j0 + N - 1 cannot overflow: j0 <= 0x3fffffff, the "no such tile" marker, masks everything)
         const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));
@@ -369,9 +369,25 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 s[e] = ok ? s[e] : LOZA_NEG_INF;
             }
         }
-        float mx = s[0];
+    };
+    auto sm_max8 = [&](const f32x16 &s, const int e0) {
+        float mx = s[e0];
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
+        for (int e = e0 + 1; e < e0 + 8; ++e) mx = fmaxf(mx, s[e]);
+        return mx;
+    };
+    auto sm_decide = [&](float mx, const float lazy) {
+        sm_up = mx > m_ref + lazy;  // also true on the first live tile (m_ref = -inf)
+        const float m_new = sm_up ? mx : m_ref;
+        sm_alpha = sm_up ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;
+        m_ref = m_new;
+        sm_m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;  // row with no live key so far
+        sm_psum = 0.f;
+        sm_rsum = 0.f;
+    };
+    auto sm_begin = [&](f32x16 &s, const int j0, const float lazy) {
+        sm_mask(s, j0);
+        float mx = fmaxf(sm_max8(s, 0), sm_max8(s, 8));
         mx = max_with_other_half(mx);
         mx *= p.scale_log2;  // scale > 0: the maximum of the scaled scores
         if (KB > 1) {
@@ -380,13 +396,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 #pragma unroll
             for (int c = 0; c < KB; ++c) mx = fmaxf(mx, s_smax[c * M + wr * 32 + ln]);
         }
-        sm_up = mx > m_ref + lazy;  // also true on the first live tile (m_ref = -inf)
-        const float m_new = sm_up ? mx : m_ref;
-        sm_alpha = sm_up ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;
-        m_ref = m_new;
-        sm_m_use = (m_new == LOZA_NEG_INF) ? 0.f : m_new;  // row with no live key so far
-        sm_psum = 0.f;
-        sm_rsum = 0.f;
+        sm_decide(mx, lazy);
     };
     auto sm_elems = [&](f32x16 &s, const int e0, const int e1) {
 #pragma unroll
@@ -396,16 +406,18 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
             sm_psum += s[e] + s[e + 1];
             sm_pk[e >> 1] = pack_bf16(s[e], s[e + 1]);
-            const float h0 = __builtin_bit_cast(float, sm_pk[e >> 1] << 16), h1 = __builtin_bit_cast(float, sm_pk[e >> 1] & 0xffff0000u);
-            sm_rsum += h0 + h1;
+            // the sum of the two rounded values, by one dot product with (1, 1)
+            const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+            sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[e >> 1]), ones, sm_rsum, false);
             if (PRECISE) {
                 // second bf16 term of each weight: what the first rounding lost
+                const float h0 = __builtin_bit_cast(float, sm_pk[e >> 1] << 16), h1 = __builtin_bit_cast(float, sm_pk[e >> 1] & 0xffff0000u);
                 sm_pk_lo[e >> 1] = pack_bf16(s[e] - h0, s[e + 1] - h1);
-                sm_rsum += __builtin_bit_cast(float, sm_pk_lo[e >> 1] << 16) + __builtin_bit_cast(float, sm_pk_lo[e >> 1] & 0xffff0000u);
+                sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[e >> 1]), ones, sm_rsum, false);
             }
         }
     };
-    auto sm_end = [&](const int pbuf) {
+    auto sm_end_fn = [&](const int pbuf) {
         l_run = l_run * sm_alpha + sm_psum;
         lr_run = lr_run * sm_alpha + sm_rsum;
         const bool rescale = __any(sm_up);
@@ -427,6 +439,59 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
         }
     };
+    // The same softmax as a list of micro-jobs, one or a few of which are issued after each matrix
+    // instruction of the value phase (KB == 1 only: no cross-wave maximum): 0 mask + maximum of
+    // scores 0..7, 1 maximum of 8..15, 2 other wavefront half + scale, 3 reference update, then
+    // per pair of scores i: 4+3i exponentials, 5+3i bf16 pack + pair sum, 6+3i running sums; last
+    // the hand-over through LDS. The empty asm statements anchor each job's results in its slot
+    // (the optimiser otherwise sinks all of this arithmetic below the last matrix instruction).
+    constexpr int SM_JOBS = 4 + 3 * 8 + 1;
+    float sm_mx = 0.f, sm_mx2 = 0.f;
+    auto sm_job = [&](const int j, f32x16 &s, const int j0, const float lazy, const int pbuf) {
+        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+        if (j == 0) {
+            sm_mask(s, j0);
+            sm_mx = sm_max8(s, 0);
+            asm volatile("" : "+v"(s), "+v"(sm_mx));
+        } else if (j == 1) {
+            sm_mx2 = sm_max8(s, 8);
+            sm_mx = fmaxf(sm_mx, sm_mx2);
+            asm volatile("" : "+v"(sm_mx));
+        } else if (j == 2) {
+            sm_mx = max_with_other_half(sm_mx) * p.scale_log2;
+            asm volatile("" : "+v"(sm_mx));
+        } else if (j == 3) {
+            sm_decide(sm_mx, lazy);
+            asm volatile("" : "+v"(sm_alpha), "+v"(sm_m_use), "+v"(m_ref));
+        } else if (j < SM_JOBS - 1) {
+            const int i = (j - 4) / 3, part = (j - 4) % 3, e = 2 * i;
+            if (part == 0) {
+                // exp2(scale*log2(e)*s - m): a dead key (s = -inf) gives exactly 0
+                s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], p.scale_log2, -sm_m_use));
+                s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
+                asm volatile("" : "+v"(s));
+            } else if (part == 1) {
+                sm_pk[i] = pack_bf16(s[e], s[e + 1]);
+                if (PRECISE) {
+                    // second bf16 term of each weight: what the first rounding lost
+                    const float h0 = __builtin_bit_cast(float, sm_pk[i] << 16), h1 = __builtin_bit_cast(float, sm_pk[i] & 0xffff0000u);
+                    sm_pk_lo[i] = pack_bf16(s[e] - h0, s[e + 1] - h1);
+                    asm volatile("" : "+v"(sm_pk_lo[i]));
+                }
+                s[e] += s[e + 1];  // the pair sum takes the place of the first value
+                asm volatile("" : "+v"(s), "+v"(sm_pk[i]));
+            } else {
+                sm_psum += s[e];
+                sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[i]), ones, sm_rsum, false);
+                if (PRECISE) sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[i]), ones, sm_rsum, false);
+                asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum));
+            }
+        } else if (j == SM_JOBS - 1) {
+            sm_end_fn(pbuf);
+        }
+    };
+    auto sm_end = [&](const int pbuf) { sm_end_fn(pbuf); };
+    (void)sm_end;
     auto softmax_tile = [&](f32x16 &s, const int j0, const int pbuf, const float lazy) {
         sm_begin(s, j0, lazy);
         sm_elems(s, 0, 16);
@@ -463,31 +528,47 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // pair are fetched from LDS while the RB matrix instructions of this pair run. With WITH_SOFTMAX
     // the softmax of the NEXT tile (scores in `s`) is cut into pieces that are issued between the
     // matrix instructions, so that the vector ALUs work in the shadow of the matrix cores.
-    auto value_tile = [&](const int stage, const int pbuf, auto with_softmax, f32x16 &s, const int j0_next,
-                          const int pbuf_next, const float lazy) {
-        constexpr bool WITH_SOFTMAX = decltype(with_softmax)::value;
+    struct ValueFrags {
+        bf16x8 pf[2][RB];      // P^T fragments of two key steps
+        s16x4 vlo[3], vhi[3];  // value fragments: two steps of look-ahead
+    };
+    constexpr int V_KS = N / 16, V_NSTEP = V_KS * C::DVB;
+    auto value_ptrs = [&](const int stage, const int pbuf, const char *&vp, const char *&pb) {
         const char *vtile = smem + stage * C::STAGE + (ALIAS ? 0 : C::KTILE);
         const int s16 = lane & 15, g16 = (lane >> 4) & 1;
-        const char *vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
-        const char *pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
-        constexpr int KS = N / 16, NSTEP = KS * C::DVB;
-        auto load_v = [&](int step, s16x4 &lo, s16x4 &hi) {
-            const char *va = vp + (step / C::DVB) * 16 * C::VROW + (step % C::DVB) * 64;
-            lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
-            hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
-        };
-        bf16x8 pf[2][RB];
-        s16x4 vlo[3], vhi[3];  // value fragments: two steps of look-ahead
-        const char *pb_lo = pb + C::PLO * C::PBYTES;
+        vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
+        pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
+    };
+    auto load_v = [&](const char *vp, int step, s16x4 &lo, s16x4 &hi) {
+        const char *va = vp + (step / C::DVB) * 16 * C::VROW + (step % C::DVB) * 64;
+        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
+        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
+    };
+    // The first fragments of a value phase. The pipelined loop requests them BEFORE the score phase,
+    // so that their LDS latency hides behind it.
+    auto value_prefetch = [&](const int stage, const int pbuf, ValueFrags &f) {
+        const char *vp, *pb;
+        value_ptrs(stage, pbuf, vp, pb);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) pf[0][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW);
-        load_v(0, vlo[0], vhi[0]);
-        if (NSTEP > 1) load_v(1, vlo[1], vhi[1]);
+        for (int rb = 0; rb < RB; ++rb) f.pf[0][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW);
+        load_v(vp, 0, f.vlo[0], f.vhi[0]);
+        if (V_NSTEP > 1) load_v(vp, 1, f.vlo[1], f.vhi[1]);
+    };
+    auto value_tile = [&](const int stage, const int pbuf, ValueFrags &f, auto with_softmax, f32x16 &s,
+                          const int j0_next, const int pbuf_next, const float lazy) {
+        constexpr bool WITH_SOFTMAX = decltype(with_softmax)::value;
+        constexpr int KS = V_KS, NSTEP = V_NSTEP;
+        const char *vp, *pb;
+        value_ptrs(stage, pbuf, vp, pb);
+        const char *pb_lo = pb + C::PLO * C::PBYTES;
+        auto &pf = f.pf;
+        auto &vlo = f.vlo;
+        auto &vhi = f.vhi;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             const int ks = step / C::DVB, db = step % C::DVB;
-            if (step + 2 < NSTEP) load_v(step + 2, vlo[(step + 2) % 3], vhi[(step + 2) % 3]);
+            if (step + 2 < NSTEP) load_v(vp, step + 2, vlo[(step + 2) % 3], vhi[(step + 2) % 3]);
             if (db == 0 && ks + 1 < KS) {
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) pf[(ks + 1) & 1][rb] = *(const bf16x8 *)(pb + rb * 32 * C::PROW + (ks + 1) * 32);
@@ -498,39 +579,21 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             a8[4] = hi[0]; a8[5] = hi[1]; a8[6] = hi[2]; a8[7] = hi[3];
             const bf16x8 a = __builtin_bit_cast(bf16x8, a8);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
+            for (int rb = 0; rb < RB; ++rb) {
                 o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[ks & 1][rb], o[db][rb], 0, 0, 0);
-            if (PRECISE) {
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
+                if (PRECISE) {
                     const bf16x8 pl = *(const bf16x8 *)(pb_lo + rb * 32 * C::PROW + ks * 32);
                     o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, o[db][rb], 0, 0, 0);
                 }
-            }
-            if (WITH_SOFTMAX) {
-                // piece `step` of the next tile's softmax: statistics first, then the 16 scores of
-                // this lane spread over the remaining steps, the LDS hand-over last
-                // (the empty asm statements anchor each piece in its step: without them the
-                // optimiser sinks all of this arithmetic below the last matrix instruction)
-                if (step == 0) {
-                    sm_begin(s, j0_next, lazy);
-                    asm volatile("" : "+v"(s), "+v"(sm_m_use), "+v"(sm_alpha));
-                }
-                if (NSTEP >= 4) {
-                    constexpr int PER = (16 / (NSTEP > 2 ? NSTEP - 2 : 1) + 1) & ~1;  // even number of scores per step
-                    if (step >= 1 && step <= NSTEP - 2) {
-                        const int e0 = (step - 1) * PER, e1 = step == NSTEP - 2 ? 16 : (e0 + PER < 16 ? e0 + PER : 16);
-                        if (e0 < 16) {
-                            sm_elems(s, e0, e1);
+                if (WITH_SOFTMAX) {
+                    // the micro-jobs of the next tile's softmax that belong to this slot
+                    constexpr int NSLOT = NSTEP * RB, JPS = (SM_JOBS + NSLOT - 1) / NSLOT;
+                    const int slot = step * RB + rb;
 #pragma unroll
-                            for (int e = e0; e < e1; e += 2) asm volatile("" : "+v"(sm_pk[e >> 1]));
-                            asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum));
-                        }
-                    }
-                } else if (step == NSTEP - 1) {
-                    sm_elems(s, 0, 16);
+                    for (int jj = 0; jj < JPS; ++jj)
+                        if (slot * JPS + jj < SM_JOBS) sm_job(slot * JPS + jj, s, j0_next, lazy, pbuf_next);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (step == NSTEP - 1) sm_end(pbuf_next);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -562,10 +625,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             // as a whole (key index "infinity"), which leaves the softmax state untouched: one
             // straight-line loop body instead of a peeled last iteration.
             const u32x4 flags = rescale_flags(u & 1);  // requested now, used after the score phase
+            ValueFrags vf;
+            value_prefetch(st_v, u & 1, vf);
+            __builtin_amdgcn_sched_barrier(0);
             if (WEAVE && u + 2 < nt) score_tile_copy(st_k, s, t_begin + u + 2, st_l);
             else score_tile(st_k, s);
             rescale_tile(u & 1, flags);
-            value_tile(st_v, u & 1, yes_t{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
+            value_tile(st_v, u & 1, vf, yes_t{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
                        u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
             const int tmp = st_v; st_v = st_k; st_k = st_l; st_l = tmp;
         }
@@ -580,8 +646,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             score_tile(stage, s);
             softmax_tile(s, key_tile(t_begin + u) * N, 0, u < p.exact_tiles ? 0.f : p.lazy_log2);
             lds_barrier();
+            ValueFrags vf;
+            value_prefetch(stage, 0, vf);
             rescale_tile(0, rescale_flags(0));
-            value_tile(stage, 0, no_t{}, s, 0, 0, 0.f);
+            value_tile(stage, 0, vf, no_t{}, s, 0, 0, 0.f);
         }
     }
 
