@@ -34,7 +34,7 @@ def body(ks: int, depth: int) -> str:
     return "".join(f'    "{l}\\n"\n' for l in lines)
 
 
-def body_copy(ks: int, depth: int, n_copy: int) -> str:
+def body_copy(ks: int, depth: int, n_copy: int, waves: int) -> str:
     """Score phase with the global -> LDS copy of a later key tile woven in: one
     global_load_lds_dwordx4 every few matrix instructions, so that issuing the copy costs the
     matrix cores nothing. Extra operands after the query fragments: n_copy per-lane byte offsets,
@@ -61,7 +61,7 @@ def body_copy(ks: int, depth: int, n_copy: int) -> str:
             lines.append(f"ds_read_b128 {t(kk % depth)}, {addr} offset:{(kk + depth) * 32}")
         if c < n_copy and kk % every == every // 2:
             lines.append(f"v_min_u32 {tmp}, {kmax}, {voff(c)}")
-            lines.append(f"s_add_u32 m0, {m0b}, {c * 4096}")
+            lines.append(f"s_add_u32 m0, {m0b}, {c * waves * 1024}")
             lines.append("s_nop 0")
             lines.append(f"global_load_lds_dwordx4 {tmp}, {src}")
             c += 1
@@ -70,17 +70,17 @@ def body_copy(ks: int, depth: int, n_copy: int) -> str:
     return "".join(f'    "{l}\\n"\n' for l in lines)
 
 
-def macro_copy(dqk: int, n_copy: int) -> str:
+def macro_copy(dqk: int, n_copy: int, waves: int) -> str:
     ks = dqk // 16
     depth = min(DEPTH, ks)
     outs = ['"=&v"(s_)'] + [f'"=&v"(kf_[{d}])' for d in range(depth)] + ['"=&v"(tmp_)']
     ins = ['"v"(addr_)'] + [f'"v"(qf_[{kk}])' for kk in range(ks)] + [f'"v"(voff_[{c}])' for c in range(n_copy)]
     ins += ['"s"(kmax_)', '"s"(src_)', '"s"(m0base_)']
-    text = f"// d_qk = {dqk}: as above, plus {n_copy} copy instructions of a later key tile\n"
-    text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
-    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy).splitlines(True))
+    text = f"// d_qk = {dqk}, {waves} waves per workgroup: as above, plus {n_copy} copy instructions of a later key tile\n"
+    text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY_W{waves}(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
+    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, waves).splitlines(True))
     text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\")\n"
-    text += f"#define LOZA_SCORE_COPIES_{dqk} {n_copy}\n"
+    text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
     return text
 
 
@@ -102,5 +102,5 @@ if __name__ == "__main__":
     print("#ifndef LOZA_SCORE_ASM_H\n#define LOZA_SCORE_ASM_H\n")
     for dqk in (576, 128):
         print(macro(dqk))
-    print(macro_copy(576, 9))
+    print(macro_copy(576, 9, 4))
     print("#endif")

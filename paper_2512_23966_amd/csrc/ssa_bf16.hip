@@ -4,22 +4,28 @@
 // (paper: Architecture section, Eq. 2 / Eq. 4; with window >= S this is Eq. 1), plus the natural
 // log of the softmax denominator.  live(i) = { j <= i : j < n_sink or i - j < window }.
 //
-// How it is mapped to the machine (one workgroup = 4 wavefronts = 1 per SIMD):
+// How it is mapped to the machine (one workgroup = 4 wavefronts = 1 per SIMD; prefill tiles hold
+// 128 query rows and all four waves score, decode tiles hold 64 rows (the heads of one token) and
+// two waves score while all four accumulate values):
 //   * Rows of a workgroup tile are (position, head-in-group) pairs of ONE key/value head, so all
 //     query heads that share a latent (absorbed MLA) reuse each key tile from a single LDS copy.
 //   * Only live key tiles are enumerated: the sink tiles, then the window tiles, by closed-form
 //     integer arithmetic (no schedule metadata in memory, the same schedule for every head).
 //     Interior tiles take no mask; only tiles cut by the causal diagonal, the window's trailing
 //     edge or the sink edge evaluate the predicate per element.
-//   * Score phase: wave (wr, wk) holds the 32 query rows of row block wr in registers as MFMA B
-//     operands and computes S^T = K Q^T for key block wk of the tile (32x32x16 bf16 MFMA), so that
+//   * Score phase: a scoring wave holds the 32 query rows of its row block in registers as MFMA B
+//     operands and computes S^T = K Q^T for the 32 keys of the tile (32x32x16 bf16 MFMA), so that
 //     one lane owns one query row and the online-softmax statistics need a single cross-lane step.
 //   * P is rounded to bf16 and handed over through LDS; in the value phase wave w owns the
 //     d_v / 4 output columns [w*d_v/4, (w+1)*d_v/4) of ALL rows of the tile, so each value
 //     fragment (read transposed from the key tile with ds_read_b64_tr_b16) is fetched once per
 //     workgroup instead of once per wave.
-//   * Key tiles stream HBM/L2 -> LDS with global_load_lds_dwordx4 (no register staging), double
-//     buffered; LDS rows are padded by 16 bytes so 128-bit fragment reads are bank-conflict free.
+//   * Key tiles stream HBM/L2 -> LDS with global_load_lds_dwordx4 (no register staging) through a
+//     ring of 3 (prefill) or 4 (decode: more bytes in flight per compute unit) stages; LDS rows
+//     are padded by 16 bytes so 128-bit fragment reads are bank-conflict free.
+//   * One barrier per tile: while the value phase of tile u runs on the matrix cores, the scores
+//     of tile u + 1 are already in registers and their softmax is issued between the matrix
+//     instructions; later tiles are in flight from global memory.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -82,22 +88,36 @@ static __device__ __forceinline__ float xor32(float x)
     return __shfl_xor(x, 32, 64);
 }
 
-template <int DQK, int DV, int RB, int KB, bool ALIAS, bool PRECISE = false>
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding:
+// vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt fields left at "no wait")
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+
+// RB: 32-row blocks per workgroup tile. Four wavefronts, one per SIMD.
+//   Prefill (RB = 4): every wave scores one row block and accumulates d_v / 4 output columns of
+//   all 128 rows.
+//   Decode (RB = 2; the 64 rows are the heads of one token): the waves specialise. Waves 0 and 1
+//   keep the queries in registers, score and run the softmax; waves 2 and 3 keep the output
+//   accumulators (d_v / 2 columns of all rows each) and run the value phase. Neither role needs
+//   the other's registers, so both fit, and the two phases of consecutive tiles overlap on
+//   different SIMDs.
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false>
 struct TileCfg {
     static constexpr int M = 32 * RB;            // query rows per workgroup
-    static constexpr int N = 32 * KB;            // keys per tile
-    static constexpr int NW = RB * KB;           // wavefronts
-    static_assert(NW == 4, "four wavefronts, one per SIMD");
-    static constexpr int DVW = DV / NW;          // output columns owned by one wave (value phase)
+    static constexpr int N = 32;                 // keys per tile
+    static constexpr int NW = 4;                 // wavefronts
+    static constexpr bool SPEC = DECODE;         // specialised roles
+    static_assert(SPEC ? RB == 2 : RB == 4, "row blocks per tile");
+    static constexpr int VW = SPEC ? 2 : 4;      // waves that accumulate values
+    static constexpr int DVW = DV / VW;          // output columns owned by one of them
     static constexpr int DVB = DVW / 32;         // 32-column blocks of them
-    static_assert(DVB * 32 * NW == DV, "d_v must be a multiple of 128");
+    static_assert(DVB * 32 * VW == DV, "d_v must be a multiple of 128");
     static_assert(DQK % 16 == 0, "d_qk must be a multiple of 16");
     static constexpr int KROW = DQK * 2 + 16;    // LDS bytes per key row (16 bytes of padding)
     static constexpr int VROW = ALIAS ? KROW : DV * 2 + 16;
     static constexpr int KCPR = KROW / 16;       // 16-byte chunks per padded key row
     static constexpr int VCPR = VROW / 16;
     // global -> LDS copy: one instruction moves 64 consecutive 16-byte chunks (1 KB) of the padded
-    // tile; instruction i belongs to wave i % 4
+    // tile; instruction i belongs to wave i % NW
     static constexpr int K_INSTR = (N * KCPR + 63) / 64;
     static constexpr int V_INSTR = ALIAS ? 0 : (N * VCPR + 63) / 64;
     static constexpr int K_PER_WAVE = (K_INSTR + NW - 1) / NW;
@@ -105,54 +125,38 @@ struct TileCfg {
     static constexpr int KTILE = K_INSTR * 1024;
     static constexpr int VTILE = V_INSTR * 1024;
     static constexpr int STAGE = KTILE + VTILE;
-    // KB == 1 (prefill): software pipeline over three tile stages and two P buffers;
-    // KB == 2 (decode): two stages, one P buffer
-    static constexpr bool PIPE = (KB == 1);
-    static constexpr int NSTAGE = PIPE ? 3 : 2;
-    // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer
-    static constexpr int NPBUF = (PIPE ? 2 : 1) * (PRECISE ? 2 : 1);
-    static constexpr int PLO = PIPE ? 2 : 1;         // index offset of the low-term buffers
+    // Ring of tile stages: tile u feeds the value phase, u + 1 the score phase, the rest is in
+    // flight. Decode is bound by HBM latency x bandwidth, so it keeps one more tile in flight.
+    static constexpr int NSTAGE = DECODE ? 4 : 3;
+    // copy instructions one wave issues per tile, at least (waves differ by at most one)
+    static constexpr int MIN_COPIES = K_INSTR / NW + V_INSTR / NW;
+    // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer pair
+    static constexpr int NPBUF = 2 * (PRECISE ? 2 : 1);
+    static constexpr int PLO = 2;                // index offset of the low-term buffers
     static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
     static constexpr int PBYTES = M * PROW;
     static constexpr int OFF_P = NSTAGE * STAGE;
-    static constexpr int OFF_ALPHA = OFF_P + NPBUF * PBYTES;      // float[NPBUF][M]
-    static constexpr int OFF_FLAG = OFF_ALPHA + NPBUF * M * 4;    // int[NPBUF][4]
-    static constexpr int OFF_SMAX = OFF_FLAG + NPBUF * 16;        // float[KB][M]
-    static constexpr int OFF_LPART = OFF_SMAX + KB * M * 4;       // float[2][KB][M]
-    static constexpr int LDS_BYTES = OFF_LPART + 2 * KB * M * 4;
+    static constexpr int OFF_ALPHA = OFF_P + NPBUF * PBYTES;      // float[2][M]
+    static constexpr int OFF_FLAG = OFF_ALPHA + 2 * M * 4;        // int[2][4] (one per row block, padded)
+    static constexpr int OFF_LPART = OFF_FLAG + 2 * 16;           // float[2][M]
+    static constexpr int LDS_BYTES = OFF_LPART + 2 * M * 4;
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
-// Byte offset, inside a key tile in global memory, of the 16-byte chunk that lane `lane` of copy
-// instruction `instr` moves. LDS slot p = instr*64 + lane is chunk (p % cpr) of padded row
-// (p / cpr); padding slots and slots past the tile fetch some valid chunk (never read back).
-static __device__ __forceinline__ uint32_t chunk_offset(int instr, int lane, int rows, int cpr, uint32_t pos_stride)
-{
-    const int p = instr * 64 + lane;
-    int row = p / cpr, c = p - row * cpr;
-    row = row < rows ? row : rows - 1;
-    c = c < cpr - 1 ? c : cpr - 2;
-    return (uint32_t)row * pos_stride + (uint32_t)c * 16u;
-}
-
-// After the first LOZA_EXACT_MAX_TILES tiles of a row, the reference maximum is only moved when the
-// tile maximum exceeds it by more than LOZA_LAZY_RESCALE_LOG2 (log2 units): the accumulator rescale
-// then almost never runs, and P stays below 2^8. Over the first tiles the reference is the exact
-// running maximum, so that the dominant weight of a row with few live keys (where the output is
-// large) is exactly 1 and carries no bf16 rounding error.
-#define LOZA_LAZY_RESCALE_LOG2 8.0f
-#define LOZA_EXACT_MAX_TILES 8
-
-template <int DQK, int DV, int RB, int KB, bool ALIAS, bool DECODE, bool PRECISE = false>
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
-    using C = TileCfg<DQK, DV, RB, KB, ALIAS, PRECISE>;
-    constexpr int M = C::M, N = C::N;
+    using C = TileCfg<DQK, DV, RB, ALIAS, DECODE, PRECISE>;
+    constexpr int M = C::M, N = C::N, NSTAGE = C::NSTAGE;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-    const int wr = wave / KB, wk = wave % KB;
+    constexpr int NW = C::NW;
+    constexpr bool SPEC = C::SPEC;
+    const bool scorer = !SPEC || wave < RB;   // this wave scores row block `wr` and runs its softmax
+    const int wr = scorer ? wave : 0;
+    const int vw = SPEC ? wave - RB : wave;   // which slice of the output columns this wave accumulates
 
     // ---- which tile of which (batch, kv head) ------------------------------------------------
     int id = blockIdx.x;
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 
     // ---- decode of an empty cache: a neutral partial ------------------------------------------
     if (DECODE && L <= 0) {
-        for (int r = tid; r < M; r += 256) {
+        for (int r = tid; r < M; r += 64 * NW) {
             if (r0 + r >= R) continue;
             const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + r0 + r;
             float *po = p.part_o + (h * p.n_splits + split) * DV;
@@ -222,71 +226,68 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // Copy instruction `instr` fills LDS slots [instr*64, instr*64 + 64) of the padded tile: slot p
     // is chunk p % cpr of row p / cpr. Within one instruction the row changes at most once, at lane
     // `lb` when a row has at least 64 chunks; lanes below it take byte offset offA + 16*lane into
-    // the global tile, the others offB + 16*lane. These three numbers are wave-uniform and live in
-    // scalar registers (wide rows are the register-starved case). Narrow rows keep one per-lane
-    // offset per instruction in vector registers instead. A padding slot fetches the chunk that
-    // follows its row in memory and slots past the tile fetch further on; both are cut to the
-    // last valid chunk below and never read back from LDS.
+    // the global tile, the others offB + 16*lane. A padding slot fetches the chunk that follows its
+    // row in memory and slots past the tile fetch further on; both are cut to the last valid chunk
+    // below and never read back from LDS.
     const uint32_t pos_stride_k = (uint32_t)p.Hkv * DQK * 2;  // bytes between consecutive positions
     const uint32_t pos_stride_v = (uint32_t)p.Hkv * DV * 2;
-    struct CopyPlan { uint32_t offA, offB; int lb; };
-    auto make_plan = [&](int instr, int cpr, uint32_t stride) {
-        CopyPlan c;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    auto copy_offset = [&](int instr, int cpr, uint32_t stride) {
         const int p0 = instr * 64, row0 = p0 / cpr, c0 = p0 - row0 * cpr;
         if (cpr >= 64) {
-            c.lb = cpr - c0;  // first lane of the next row (>= 64: no row change inside)
-            c.offA = (uint32_t)row0 * stride + (uint32_t)c0 * 16u;
-            c.offB = (uint32_t)(row0 + 1) * stride - (uint32_t)c.lb * 16u;
-        } else {
-            const int pl = p0 + lane, row = pl / cpr;
-            c.lb = 64;
-            c.offA = (uint32_t)row * stride + (uint32_t)(pl - row * cpr) * 16u - lane16_of(lane);
-            c.offB = c.offA;
+            const int lb = cpr - c0;  // first lane of the next row (>= 64: no row change inside)
+            const uint32_t offA = (uint32_t)row0 * stride + (uint32_t)c0 * 16u;
+            const uint32_t offB = (uint32_t)(row0 + 1) * stride - (uint32_t)lb * 16u;
+            return (lane < lb ? offA : offB) + lane16;
         }
-        return c;
+        const int pl = p0 + lane, row = pl / cpr;
+        return (uint32_t)row * stride + (uint32_t)(pl - row * cpr) * 16u;
     };
-    CopyPlan kplan[C::K_PER_WAVE];
+    (void)lane16_of;
+    uint32_t kvoff[C::K_PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < C::K_PER_WAVE; ++u) kplan[u] = make_plan(u * 4 + wave, C::KCPR, pos_stride_k);
-    CopyPlan vplan[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
+    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(u * NW + wave, C::KCPR, pos_stride_k);
+    uint32_t vvoff[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
 #pragma unroll
-    for (int u = 0; u < C::V_PER_WAVE; ++u) vplan[u] = make_plan(u * 4 + wave, C::VCPR, pos_stride_v);
-    const uint32_t lane16 = (uint32_t)lane * 16u;
+    for (int u = 0; u < C::V_PER_WAVE; ++u) vvoff[u] = copy_offset(u * NW + wave, C::VCPR, pos_stride_v);
 
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
     const char *kbase = (const char *)p.k + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DQK * 2;
     const char *vbase = (const char *)p.v + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DV * 2;
 
-    // per-lane byte offsets of this wave's copy instructions (before the cut to the last valid chunk)
-    uint32_t kvoff[C::K_PER_WAVE];
-#pragma unroll
-    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = (lane < kplan[u].lb ? kplan[u].offA : kplan[u].offB) + lane16;
-
-    auto issue_tile = [&](int t, int stage) {
+    // One global -> LDS copy instruction: 64 lanes x 16 bytes from base + off (per lane) to the 1 KB
+    // of LDS at lds_addr (wave-uniform, through M0). Spelled out in asm so that the compiler's
+    // wait-count bookkeeping does not know about it: it would otherwise drain every copy in flight
+    // (vmcnt(0)) before the next LDS read, and the tile loop waits with explicit counts instead.
+    auto copy_1k = [&](const char *base, uint32_t off, uint32_t lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n s_nop 0\n global_load_lds_dwordx4 %0, %1"
+                     :: "v"(off), "s"(base), "s"(lds_addr) : "memory", "m0");
+    };
+    // this wave's copy instructions [u_first, ...) of key tile t into `stage`
+    auto issue_tile = [&](int t, int stage, int u_first) {
         const int64_t j0 = (int64_t)key_tile(t) * N;
         // rows of the tile at or past the sequence end fetch from its last valid row instead:
         // they are dead (j > i) and only have to be finite
         const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
         const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
-        char *kdst = smem + stage * C::STAGE + wave * 1024;
+        const uint32_t kdst = smem_lds + stage * C::STAGE + wave * 1024;
         const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
 #pragma unroll
         for (int u = 0; u < C::K_PER_WAVE; ++u) {
-            if ((u + 1) * 4 <= C::K_INSTR || u * 4 + wave < C::K_INSTR) {  // wave-uniform
-                uint32_t off = (lane < kplan[u].lb ? kplan[u].offA : kplan[u].offB) + lane16;
-                off = off < kmax ? off : kmax;
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + off), (lds_void_ptr)(kdst + u * 4096), 16, 0, 0);
+            if (u >= u_first && ((u + 1) * NW <= C::K_INSTR || u * NW + wave < C::K_INSTR)) {  // wave-uniform
+                const uint32_t off = kvoff[u] < kmax ? kvoff[u] : kmax;
+                copy_1k(ksrc, off, kdst + u * (NW * 1024));
             }
         }
         if (!ALIAS) {
             const char *vsrc = vbase + j0 * (int64_t)pos_stride_v;
-            char *vdst = smem + stage * C::STAGE + C::KTILE + wave * 1024;
+            const uint32_t vdst = smem_lds + stage * C::STAGE + C::KTILE + wave * 1024;
             const uint32_t vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
 #pragma unroll
             for (int u = 0; u < C::V_PER_WAVE; ++u) {
-                if ((u + 1) * 4 <= C::V_INSTR || u * 4 + wave < C::V_INSTR) {
-                    uint32_t off = (lane < vplan[u].lb ? vplan[u].offA : vplan[u].offB) + lane16;
-                    off = off < vmax ? off : vmax;
-                    __builtin_amdgcn_global_load_lds((glb_void_ptr)(vsrc + off), (lds_void_ptr)(vdst + u * 4096), 16, 0, 0);
+                if ((u + 1) * NW <= C::V_INSTR || u * NW + wave < C::V_INSTR) {
+                    const uint32_t off = vvoff[u] < vmax ? vvoff[u] : vmax;
+                    copy_1k(vsrc, off, vdst + u * (NW * 1024));
                 }
             }
         }
@@ -307,39 +308,33 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 
     float *s_alpha = (float *)(smem + C::OFF_ALPHA);
     int *s_flag = (int *)(smem + C::OFF_FLAG);
-    float *s_smax = (float *)(smem + C::OFF_SMAX);
     float *s_lpart = (float *)(smem + C::OFF_LPART);
     char *s_p = smem + C::OFF_P;
+    if (tid < 8) s_flag[tid] = 0;  // the padding entries of the flag words never ask for a rescale
 
-    // ---- scores of one tile: S^T[32 keys of block wk][32 rows of block wr] ---------------------------
+    // ---- scores of one tile: S^T[32 keys][32 rows of block wr] ------------------------------------
     // One inline-asm statement (score_asm.h): key fragment kk + DEPTH is fetched from LDS while
     // fragment kk feeds the matrix core, with the exact lgkmcnt each step needs. The accumulator is
     // in VGPRs (the AGPR half of the register file is full of O).
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+    constexpr bool WEAVE = (DQK == 576 && ALIAS);  // copy instructions woven into the score phase
     // The same with the copy of key tile `t_copy` into stage `stage_copy` woven in (wide rows only):
     // the copy instructions issue between matrix instructions instead of ahead of them.
     auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy) {
-        if constexpr (DQK == 576 && ALIAS && C::PIPE) {
-            const uint32_t kaddr = smem_lds + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
+        if constexpr (WEAVE) {
+            const uint32_t kaddr = smem_lds + stage * C::STAGE + ln * C::KROW + lh * 16;
             const int64_t j0 = (int64_t)key_tile(t_copy) * N;
             const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
             const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
             const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
             const uint32_t m0base = smem_lds + stage_copy * C::STAGE + wave * 1024;
-            static_assert(LOZA_SCORE_COPIES_576 * 4 <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576 + 1, "copy plan");
+            static_assert(!WEAVE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
             uint32_t tmp;
-            LOZA_SCORE_PHASE_576_COPY(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
-            // the instruction past the woven ones exists for the first waves only
-            if (LOZA_SCORE_COPIES_576 < C::K_PER_WAVE && LOZA_SCORE_COPIES_576 * 4 + wave < C::K_INSTR) {
-                const uint32_t off = kvoff[C::K_PER_WAVE - 1] < kmax ? kvoff[C::K_PER_WAVE - 1] : kmax;
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(ksrc + off),
-                                                 (lds_void_ptr)(smem + stage_copy * C::STAGE + wave * 1024 + LOZA_SCORE_COPIES_576 * 4096), 16, 0, 0);
-            }
+            LOZA_SCORE_PHASE_576_COPY_W4(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
         }
     };
     auto score_tile = [&](int stage, f32x16 &s) {
-        const uint32_t kaddr = smem_lds + stage * C::STAGE + (wk * 32 + ln) * C::KROW + lh * 16;
+        const uint32_t kaddr = smem_lds + stage * C::STAGE + ln * C::KROW + lh * 16;
         static_assert(DQK == 576 || DQK == 128, "add a LOZA_SCORE_PHASE for this d_qk");
         if constexpr (DQK == 576) {
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
@@ -350,9 +345,8 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         }
     };
 
-    // ---- mask + online softmax of one tile, in three parts so that the value phase can run them
-    //      between its matrix instructions; P (bf16), alpha and the rescale flag go to LDS -------------
-    float sm_m_use = 0.f, sm_alpha = 1.f, sm_psum = 0.f, sm_rsum = 0.f;
+    // ---- mask + online softmax of one tile; P (bf16), alpha and the rescale flag go to LDS ----------
+    float sm_m_use = 0.f, sm_alpha = 1.f, sm_psum = 0.f, sm_rsum = 0.f, sm_mx = 0.f;
     bool sm_up = false;
     uint32_t sm_pk[8];
     uint32_t sm_pk_lo[PRECISE ? 8 : 1];
@@ -361,7 +355,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         // (j0 + N - 1 cannot overflow: j0 <= 0x3fffffff, the "no such tile" marker, masks everything)
         const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));
         if (!interior) {
-            const int jb = j0 + wk * 32 + 4 * lh;
+            const int jb = j0 + 4 * lh;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int j = jb + 8 * (e >> 2) + (e & 3);
@@ -385,47 +379,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         sm_psum = 0.f;
         sm_rsum = 0.f;
     };
-    auto sm_begin = [&](f32x16 &s, const int j0, const float lazy) {
-        sm_mask(s, j0);
-        float mx = fmaxf(sm_max8(s, 0), sm_max8(s, 8));
-        mx = max_with_other_half(mx);
-        mx *= p.scale_log2;  // scale > 0: the maximum of the scaled scores
-        if (KB > 1) {
-            if (lh == 0) s_smax[wk * M + wr * 32 + ln] = mx;
-            lds_barrier();
-#pragma unroll
-            for (int c = 0; c < KB; ++c) mx = fmaxf(mx, s_smax[c * M + wr * 32 + ln]);
-        }
-        sm_decide(mx, lazy);
-    };
-    auto sm_elems = [&](f32x16 &s, const int e0, const int e1) {
-#pragma unroll
-        for (int e = e0; e < e1; e += 2) {
-            // exp2(scale*log2(e)*s - m): a dead key (s = -inf) gives exactly 0
-            s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], p.scale_log2, -sm_m_use));
-            s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
-            sm_psum += s[e] + s[e + 1];
-            sm_pk[e >> 1] = pack_bf16(s[e], s[e + 1]);
-            // the sum of the two rounded values, by one dot product with (1, 1)
-            const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
-            sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[e >> 1]), ones, sm_rsum, false);
-            if (PRECISE) {
-                // second bf16 term of each weight: what the first rounding lost
-                const float h0 = __builtin_bit_cast(float, sm_pk[e >> 1] << 16), h1 = __builtin_bit_cast(float, sm_pk[e >> 1] & 0xffff0000u);
-                sm_pk_lo[e >> 1] = pack_bf16(s[e] - h0, s[e + 1] - h1);
-                sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[e >> 1]), ones, sm_rsum, false);
-            }
-        }
-    };
     auto sm_end_fn = [&](const int pbuf) {
         l_run = l_run * sm_alpha + sm_psum;
         lr_run = lr_run * sm_alpha + sm_rsum;
         const bool rescale = __any(sm_up);
-        if (wk == 0) {
-            if (lane == 0) s_flag[pbuf * 4 + wr] = rescale ? 1 : 0;
-            if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = sm_alpha;
-        }
-        char *pp = s_p + pbuf * C::PBYTES + (wr * 32 + ln) * C::PROW + (wk * 32 + 4 * lh) * 2;
+        if (lane == 0) s_flag[pbuf * 4 + wr] = rescale ? 1 : 0;
+        if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = sm_alpha;
+        char *pp = s_p + pbuf * C::PBYTES + (wr * 32 + ln) * C::PROW + (4 * lh) * 2;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             u32x2 w;
@@ -439,14 +399,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
         }
     };
-    // The same softmax as a list of micro-jobs, one or a few of which are issued after each matrix
-    // instruction of the value phase (KB == 1 only: no cross-wave maximum): 0 mask + maximum of
-    // scores 0..7, 1 maximum of 8..15, 2 other wavefront half + scale, 3 reference update, then
-    // per pair of scores i: 4+3i exponentials, 5+3i bf16 pack + pair sum, 6+3i running sums; last
-    // the hand-over through LDS. The empty asm statements anchor each job's results in its slot
-    // (the optimiser otherwise sinks all of this arithmetic below the last matrix instruction).
+    // The softmax as a list of micro-jobs, one or a few of which are issued after each matrix
+    // instruction of the value phase: 0 mask + maximum of scores 0..7, 1 maximum of 8..15, 2 other
+    // wavefront half + scale, 3 reference update, then per pair of scores i: 4+3i exponentials,
+    // 5+3i bf16 pack + pair sum, 6+3i running sums; last the hand-over through LDS. The empty asm
+    // statements anchor each job's results in its slot (the optimiser otherwise sinks all of this
+    // arithmetic below the last matrix instruction).
     constexpr int SM_JOBS = 4 + 3 * 8 + 1;
-    float sm_mx = 0.f, sm_mx2 = 0.f;
     auto sm_job = [&](const int j, f32x16 &s, const int j0, const float lazy, const int pbuf) {
         const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
         if (j == 0) {
@@ -454,11 +413,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             sm_mx = sm_max8(s, 0);
             asm volatile("" : "+v"(s), "+v"(sm_mx));
         } else if (j == 1) {
-            sm_mx2 = sm_max8(s, 8);
-            sm_mx = fmaxf(sm_mx, sm_mx2);
+            sm_mx = fmaxf(sm_mx, sm_max8(s, 8));
             asm volatile("" : "+v"(sm_mx));
         } else if (j == 2) {
-            sm_mx = max_with_other_half(sm_mx) * p.scale_log2;
+            sm_mx = max_with_other_half(sm_mx) * p.scale_log2;  // scale > 0: maximum of the scaled scores
             asm volatile("" : "+v"(sm_mx));
         } else if (j == 3) {
             sm_decide(sm_mx, lazy);
@@ -482,6 +440,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 asm volatile("" : "+v"(s), "+v"(sm_pk[i]));
             } else {
                 sm_psum += s[e];
+                // the sum of the two rounded values, by one dot product with (1, 1)
                 sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[i]), ones, sm_rsum, false);
                 if (PRECISE) sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[i]), ones, sm_rsum, false);
                 asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum));
@@ -490,12 +449,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             sm_end_fn(pbuf);
         }
     };
-    auto sm_end = [&](const int pbuf) { sm_end_fn(pbuf); };
-    (void)sm_end;
     auto softmax_tile = [&](f32x16 &s, const int j0, const int pbuf, const float lazy) {
-        sm_begin(s, j0, lazy);
-        sm_elems(s, 0, 16);
-        sm_end(pbuf);
+#pragma unroll
+        for (int j = 0; j < SM_JOBS; ++j) sm_job(j, s, j0, lazy, pbuf);
     };
 
     // ---- accumulator rescale of one tile (rare after the first tiles) -----------------------------------
@@ -524,9 +480,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
 
     // ---- values of one tile: O^T[d_v slice of this wave][all rows] += V^T P^T -------------------------
-    // Explicit software pipeline over the (key step, column block) pairs: the fragments of the next
-    // pair are fetched from LDS while the RB matrix instructions of this pair run. With WITH_SOFTMAX
-    // the softmax of the NEXT tile (scores in `s`) is cut into pieces that are issued between the
+    // Explicit software pipeline over the (key step, column block) pairs: the value fragments of the
+    // pair after next are fetched from LDS while the RB matrix instructions of this pair run. On a
+    // scoring wave the softmax of the NEXT tile (scores in `s`) is issued as micro-jobs between the
     // matrix instructions, so that the vector ALUs work in the shadow of the matrix cores.
     struct ValueFrags {
         bf16x8 pf[2][RB];      // P^T fragments of two key steps
@@ -536,7 +492,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     auto value_ptrs = [&](const int stage, const int pbuf, const char *&vp, const char *&pb) {
         const char *vtile = smem + stage * C::STAGE + (ALIAS ? 0 : C::KTILE);
         const int s16 = lane & 15, g16 = (lane >> 4) & 1;
-        vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (wave * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
+        vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (vw * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
         pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
     };
     auto load_v = [&](const char *vp, int step, s16x4 &lo, s16x4 &hi) {
@@ -544,8 +500,8 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va));
         hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(va + 4 * C::VROW));
     };
-    // The first fragments of a value phase. The pipelined loop requests them BEFORE the score phase,
-    // so that their LDS latency hides behind it.
+    // The first fragments of a value phase, requested BEFORE the score phase so that their LDS
+    // latency hides behind it.
     auto value_prefetch = [&](const int stage, const int pbuf, ValueFrags &f) {
         const char *vp, *pb;
         value_ptrs(stage, pbuf, vp, pb);
@@ -585,106 +541,134 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                     const bf16x8 pl = *(const bf16x8 *)(pb_lo + rb * 32 * C::PROW + ks * 32);
                     o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, o[db][rb], 0, 0, 0);
                 }
+                // the micro-jobs of the next tile's softmax that belong to this slot
+                constexpr int NSLOT = NSTEP * RB, JPS = (SM_JOBS + NSLOT - 1) / NSLOT;
+                const int slot = step * RB + rb;
                 if (WITH_SOFTMAX) {
-                    // the micro-jobs of the next tile's softmax that belong to this slot
-                    constexpr int NSLOT = NSTEP * RB, JPS = (SM_JOBS + NSLOT - 1) / NSLOT;
-                    const int slot = step * RB + rb;
 #pragma unroll
                     for (int jj = 0; jj < JPS; ++jj)
                         if (slot * JPS + jj < SM_JOBS) sm_job(slot * JPS + jj, s, j0_next, lazy, pbuf_next);
-                    __builtin_amdgcn_sched_barrier(0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    using yes_t = std::true_type;
-    using no_t = std::false_type;
 
+    // ---- the tile loop: one barrier per tile ------------------------------------------------------------
+    // Tile u (ring stage u % NSTAGE) feeds the value phase while the scores of tile u + 1 are taken
+    // and tile u + NSTAGE - 1 starts its way from global memory; tiles in between are in flight.
+    // Past the last tile the score phase runs on a stale stage and its result is masked out as a
+    // whole (key index "infinity"), which leaves the softmax state untouched: one straight-line
+    // loop body instead of a peeled last iteration.
     const int nt = t_end - t_begin;
-    if (C::PIPE) {
-        // Software pipeline, one barrier per tile: while the value phase of tile u runs on the
-        // matrix cores, the scores of tile u + 1 are already in registers and their softmax runs on
-        // the vector ALUs; tile u + 2 is in flight from global memory.
-        f32x16 s;
-        if (nt > 0) {
-            issue_tile(t_begin, 0);
-            if (nt > 1) issue_tile(t_begin + 1, 1);
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-            lds_barrier();
+    constexpr int AHEAD = NSTAGE - 1;  // tiles requested ahead of the one in the value phase
+    f32x16 s;
+    if (nt > 0) {
+#pragma unroll
+        for (int a = 0; a < AHEAD; ++a)
+            if (a < nt) issue_tile(t_begin + a, a, 0);
+        // tile 0 has landed when at most the copies of the later ones are outstanding
+        if (nt >= AHEAD) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 1) * C::MIN_COPIES));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        lds_barrier();
+        if (scorer) {
             score_tile(0, s);
             softmax_tile(s, key_tile(t_begin) * N, 0, 0.f);
         }
-        int st_v = 0, st_k = 1, st_l = 2;  // stage of tile u (values), u + 1 (scores), u + 2 (load)
+    }
+    auto top_of_tile = [&](int u) {
+        // this wave's share of tile u + 1 has landed when at most the copies of the tiles after it
+        // are outstanding
+        if (u + AHEAD <= nt) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 2) * C::MIN_COPIES));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        lds_barrier();  // ... everyone's; P of tile u is visible; the stage of tile u - 1 is free
+    };
+    constexpr int WOVEN = LOZA_SCORE_COPIES_576_W4;
+    if (!SPEC) {
+        int st_v = 0;  // ring stage of tile u
         for (int u = 0; u < nt; ++u) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u + 1 has landed
-            lds_barrier();                     // ... everyone's; P of tile u is visible; stage st_l is free
-            constexpr bool WEAVE = (DQK == 576 && ALIAS && C::PIPE);  // copy instructions inside the score phase
-            if (!WEAVE && u + 2 < nt) issue_tile(t_begin + u + 2, st_l);
-            // Past the last tile the score phase runs on a stale stage and its result is masked out
-            // as a whole (key index "infinity"), which leaves the softmax state untouched: one
-            // straight-line loop body instead of a peeled last iteration.
+            top_of_tile(u);
+            const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
+            const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;  // = (u + AHEAD) % NSTAGE
+            const bool more = u + AHEAD < nt;
             const u32x4 flags = rescale_flags(u & 1);  // requested now, used after the score phase
             ValueFrags vf;
             value_prefetch(st_v, u & 1, vf);
             __builtin_amdgcn_sched_barrier(0);
-            if (WEAVE && u + 2 < nt) score_tile_copy(st_k, s, t_begin + u + 2, st_l);
-            else score_tile(st_k, s);
+            if (WEAVE && more) {
+                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l);
+                issue_tile(t_begin + u + AHEAD, st_l, WOVEN);  // what was not woven in
+            } else {
+                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0);
+                score_tile(st_k, s);
+            }
             rescale_tile(u & 1, flags);
-            value_tile(st_v, u & 1, vf, yes_t{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
-                       u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
-            const int tmp = st_v; st_v = st_k; st_k = st_l; st_l = tmp;
+            value_tile(st_v, u & 1, vf, std::true_type{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff,
+                       (u + 1) & 1, u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
+            st_v = st_k;
+        }
+    } else if (scorer) {
+        // scoring role: while the value waves work on tile u, take the scores of tile u + 1 and hand
+        // its P over through LDS
+        int st_v = 0;
+        for (int u = 0; u < nt; ++u) {
+            top_of_tile(u);
+            const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
+            const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
+            const bool more = u + AHEAD < nt;
+            if (WEAVE && more) {
+                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l);
+                issue_tile(t_begin + u + AHEAD, st_l, WOVEN);
+            } else {
+                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0);
+                score_tile(st_k, s);
+            }
+            softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
+                         u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
+            st_v = st_k;
         }
     } else {
-        f32x16 s;
-        if (nt > 0) issue_tile(t_begin, 0);
+        // value role
+        int st_v = 0;
         for (int u = 0; u < nt; ++u) {
-            const int stage = u & 1;
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile u has landed
-            lds_barrier();                     // ... and everyone's; the other stage and P are free
-            if (u + 1 < nt) issue_tile(t_begin + u + 1, stage ^ 1);
-            score_tile(stage, s);
-            softmax_tile(s, key_tile(t_begin + u) * N, 0, u < p.exact_tiles ? 0.f : p.lazy_log2);
-            lds_barrier();
+            top_of_tile(u);
+            const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
+            const u32x4 flags = rescale_flags(u & 1);
             ValueFrags vf;
-            value_prefetch(stage, 0, vf);
-            rescale_tile(0, rescale_flags(0));
-            value_tile(stage, 0, vf, no_t{}, s, 0, 0, 0.f);
+            value_prefetch(st_v, u & 1, vf);
+            if (u + AHEAD < nt) issue_tile(t_begin + u + AHEAD, st_l, 0);
+            rescale_tile(u & 1, flags);
+            value_tile(st_v, u & 1, vf, std::false_type{}, s, 0, 0, 0.f);
+            st_v = st_v + 1 < NSTAGE ? st_v + 1 : 0;
         }
     }
 
     // ---- epilogue ----------------------------------------------------------------------------------
-    {
+    if (scorer) {
         const float l_lane = l_run + xor32(l_run);
         const float lr_lane = lr_run + xor32(lr_run);
         if (lh == 0) {
-            s_lpart[wk * M + wr * 32 + ln] = l_lane;
-            s_lpart[(KB + wk) * M + wr * 32 + ln] = lr_lane;
+            s_lpart[wr * 32 + ln] = l_lane;
+            s_lpart[M + wr * 32 + ln] = lr_lane;
         }
     }
     lds_barrier();
-    float l_tot_mine = 0.f;
-#pragma unroll
-    for (int c = 0; c < KB; ++c) l_tot_mine += s_lpart[c * M + wr * 32 + ln];
 
     if (!DECODE) {
         // lse = ln(sum_j exp(scale q.k_j)) = (m_ref + log2 l) * ln 2
-        if (wk == 0 && lh == 0 && my_row < R) {
+        if (scorer && lh == 0 && my_row < R) {
             const int hh = (int)(my_row - (int64_t)i_row * G);
             p.lse[((int64_t)b * p.Hq + (int64_t)g * G + hh) * p.S + i_row] =
-                (m_ref + __builtin_amdgcn_logf(l_tot_mine)) * 0.69314718055994530942f;
+                (m_ref + __builtin_amdgcn_logf(s_lpart[wr * 32 + ln])) * 0.69314718055994530942f;
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             const int64_t row = r0 + rb * 32 + ln;
-            float lr_tot = 0.f;
-#pragma unroll
-            for (int c = 0; c < KB; ++c) lr_tot += s_lpart[(KB + c) * M + rb * 32 + ln];
-            const float inv = 1.0f / lr_tot;
+            const float inv = 1.0f / s_lpart[M + rb * 32 + ln];
             if (row < R) {
                 const int64_t i = row / G;
                 const int hh = (int)(row - i * G);
-                uint16_t *op = p.out + ((((int64_t)b * p.S + i) * p.Hq + (int64_t)g * G + hh) * DV) + wave * C::DVW + 4 * lh;
+                uint16_t *op = p.out + ((((int64_t)b * p.S + i) * p.Hq + (int64_t)g * G + hh) * DV) + vw * C::DVW + 4 * lh;
 #pragma unroll
                 for (int db = 0; db < C::DVB; ++db)
 #pragma unroll
@@ -698,21 +682,18 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         }
     } else {
         // partial result of this key split: unnormalised O (relative to m_ref), m_ref, l, rounded l
-        if (wk == 0 && lh == 0 && my_row < R) {
+        if (scorer && lh == 0 && my_row < R) {
             const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + my_row;
-            float lr_tot_mine = 0.f;
-#pragma unroll
-            for (int c = 0; c < KB; ++c) lr_tot_mine += s_lpart[(KB + c) * M + wr * 32 + ln];
             p.part_ml[(h * p.n_splits + split) * 4 + 0] = m_ref;
-            p.part_ml[(h * p.n_splits + split) * 4 + 1] = l_tot_mine;
-            p.part_ml[(h * p.n_splits + split) * 4 + 2] = lr_tot_mine;
+            p.part_ml[(h * p.n_splits + split) * 4 + 1] = s_lpart[wr * 32 + ln];
+            p.part_ml[(h * p.n_splits + split) * 4 + 2] = s_lpart[M + wr * 32 + ln];
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             const int64_t row = r0 + rb * 32 + ln;
-            if (row < R) {
+            if (!scorer && row < R) {
                 const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + row;
-                float *op = p.part_o + (h * p.n_splits + split) * DV + wave * C::DVW + 4 * lh;
+                float *op = p.part_o + (h * p.n_splits + split) * DV + vw * C::DVW + 4 * lh;
 #pragma unroll
                 for (int db = 0; db < C::DVB; ++db)
 #pragma unroll
@@ -778,8 +759,8 @@ template <int DQK, int DV, bool ALIAS, bool PRECISE>
 static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
 {
     if (rt_count <= 0) return hipSuccess;
-    using C = TileCfg<DQK, DV, 4, 1, ALIAS, PRECISE>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 4, 1, ALIAS, false, PRECISE>;
+    using C = TileCfg<DQK, DV, 4, ALIAS, false, PRECISE>;
+    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     p.rt_begin = rt_begin;
@@ -804,8 +785,8 @@ static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
 template <int DQK, int DV, bool ALIAS>
 static hipError_t launch_decode_t(const FwdParams &p, hipStream_t stream)
 {
-    using C = TileCfg<DQK, DV, 2, 2, ALIAS>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 2, 2, ALIAS, true>;
+    using C = TileCfg<DQK, DV, 2, ALIAS, true>;
+    auto kern = ssa_fwd_kernel<DQK, DV, 2, ALIAS, true>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int64_t blocks = (int64_t)p.n_splits * p.row_tiles * p.Hkv * p.B;
