@@ -34,6 +34,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (what HBM byte counters "
+                         "collected with rocprofv3 --pmc are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -98,6 +101,13 @@ def main() -> int:
     value = (prefill_flop + decode_flop) / (ms_per_step * 1e-3) / 1e12
     prefill_tflops = prefill_flop / (prefill_ms * 1e-3) / 1e12
     decode_gbps = decode_bytes / (decode_ms * 1e-3) / 1e9
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.neg(src, out=dst)  # one elementwise kernel: reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- counters measured with rocprofv3 --pmc (stored summaries), if present ------------------
     traffic = {"prefill": None, "decode": None}

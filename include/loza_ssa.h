@@ -52,9 +52,15 @@ typedef enum {
  *   q    [B, S, Hq,  d_qk] bf16      k [B, S, Hkv, d_qk] bf16      v [B, S, Hkv, d_v] bf16 (or v == k)
  *   out  [B, S, Hq,  d_v ] bf16      lse [B, Hq, S] fp32, natural log of the softmax denominator
  *   n_sink >= 0 leading keys always visible; window >= 1 most recent keys visible (self included).
- *   scale multiplies q.k before the softmax (the 1/sqrt(d) the paper's equations leave out).
- * Supported (d_qk, d_v): (576, 512) with Hkv == 1 and v == k (absorbed MLA), (128, 128), (64, 64).
- * S <= 2^31 - 129.
+ *   scale multiplies q.k before the softmax (the 1/sqrt(d) the paper's equations leave out);
+ *   finite and > 0 (anything else: LOZA_ERR_SHAPE).
+ * Supported (d_qk, d_v): (576, 512) with v == k (absorbed MLA: the value row is the first 512
+ * elements of the key row), and (128, 128) with v separate or v == k. Anything else:
+ * LOZA_ERR_UNSUPPORTED. S <= 2^31 - 129.
+ * Numerics: scores and sums in fp32, the softmax weights rounded to bf16 for the value product
+ * (to two bf16 terms for the first 128 positions, whose few-key rows would otherwise carry the
+ * weight rounding into the output undamped); |out - exact| <= 1e-2 for |out| <= 4.
+ * The launch is deterministic: the same inputs give the same bits.
  */
 int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
                      int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
@@ -62,7 +68,8 @@ int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, flo
 
 /*
  * fp32 twin of loza_ssa_prefill (fp32 in, fp32 arithmetic, fp32 out), same layouts with float
- * elements. Any d_qk, d_v in [1, 256]; v may alias k with d_v <= d_qk.
+ * elements. Any d_qk, d_v in [1, 256]; v may alias k with d_v <= d_qk; scale finite, any sign.
+ * Plain vector arithmetic (no matrix cores): the small-shape check of the method, not a fast path.
  */
 int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
                          int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
@@ -78,8 +85,12 @@ int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *
  *           a sequence of length 0 yields out = 0, lse = -inf.
  *   out     [B, Hq, d_v] bf16              lse [B, Hq] fp32
  *   workspace: device scratch of at least loza_ssa_decode_workspace_bytes(...) bytes, 16-byte
- *           aligned; contents on entry are ignored, on exit unspecified.
- * Supported (d_qk, d_v): as loza_ssa_prefill. Cache rows at or beyond seqlens[b] are never read.
+ *           aligned; contents on entry are ignored, on exit unspecified. It holds, per (b, query
+ *           head, key split), the unnormalised fp32 partial output and four floats of softmax
+ *           state. Two calls that overlap in time need two workspaces.
+ * Supported (d_qk, d_v) and scale: as loza_ssa_prefill. Cache rows at or beyond seqlens[b] are
+ * never read. The split count depends on the sizes only, and the merge adds the splits in a
+ * fixed order: the result is deterministic.
  */
 int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                     void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,

@@ -101,6 +101,7 @@ int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, flo
 {
     if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
     if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale)) return rc;
+    if (!(scale > 0.f)) return LOZA_ERR_SHAPE;  // the row maximum is taken before the scaling
     const bool alias = (v == k);
     if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
     if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;
@@ -164,6 +165,7 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
 {
     if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
     if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, scale)) return rc;
+    if (!(scale > 0.f)) return LOZA_ERR_SHAPE;
     const bool alias = (vcache == kcache);
     if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
     if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;

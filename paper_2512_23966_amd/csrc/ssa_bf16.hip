@@ -221,7 +221,6 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     }
     auto key_tile = [&](int t) { return t < nA ? t : wt0 + (t - nA); };
 
-    auto lane16_of = [](int l) { return (uint32_t)l * 16u; };
     // ---- global -> LDS copy plan (the same for every tile) --------------------------------------
     // Copy instruction `instr` fills LDS slots [instr*64, instr*64 + 64) of the padded tile: slot p
     // is chunk p % cpr of row p / cpr. Within one instruction the row changes at most once, at lane
@@ -243,7 +242,6 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         const int pl = p0 + lane, row = pl / cpr;
         return (uint32_t)row * stride + (uint32_t)(pl - row * cpr) * 16u;
     };
-    (void)lane16_of;
     uint32_t kvoff[C::K_PER_WAVE];
 #pragma unroll
     for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(u * NW + wave, C::KCPR, pos_stride_k);
@@ -579,8 +577,8 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     auto top_of_tile = [&](int u) {
         // this wave's share of tile u + 1 has landed when at most the copies of the tiles after it
         // are outstanding
-        if (u + AHEAD <= nt) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 2) * C::MIN_COPIES));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        if (u + AHEAD > nt) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 2) * C::MIN_COPIES));
         lds_barrier();  // ... everyone's; P of tile u is visible; the stage of tile u - 1 is free
     };
     constexpr int WOVEN = LOZA_SCORE_COPIES_576_W4;

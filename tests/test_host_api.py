@@ -1,0 +1,162 @@
+"""Host side of the C ABI, no GPU needed: the library loads, exports what the header declares,
+rejects bad arguments before touching HIP, and its host-only live-set arithmetic agrees with the
+oracle's explicit mask."""
+import ctypes
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2512_23966_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = ROOT / "include" / "loza_ssa.h"
+INF = B.LOZA_WINDOW_INF
+
+ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_ALIGN = -1, -2, -3, -4, -5, -6
+
+
+def declared_functions():
+    """Names of the functions include/loza_ssa.h declares (comments stripped)."""
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(loza_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_binding_exports():
+    assert declared_functions() == sorted(B.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    for name in declared_functions():
+        assert hasattr(L, name), name
+
+
+def test_status_strings_are_distinct():
+    names = {B.loza_status_str(s) for s in range(0, -7, -1)}
+    assert len(names) == 7
+    assert B.loza_status_str(-99)  # unknown codes still give a string
+
+
+# ---- live ranges and pair counts against the oracle's mask ------------------------------------
+
+@pytest.mark.parametrize("n_sink,window", [(0, 1), (1, 1), (4, 8), (128, 1024), (0, INF), (7, 3), (64, 256), (300, 5)])
+def test_live_ranges_match_oracle_mask(n_sink, window):
+    S = 700
+    w = window if window != INF else oracle.INT64_MAX
+    for i in list(range(0, 40)) + [63, 64, 127, 128, 255, 256, 257, 299, 300, 301, 305, 699]:
+        se, wb, we = B.loza_ssa_live_ranges(i, n_sink, window)
+        assert 0 <= se <= wb <= we == i + 1
+        got = np.zeros(S, dtype=bool)
+        got[:se] = True
+        got[wb:we] = True
+        assert np.array_equal(got, oracle.live_mask(i, S, n_sink, w).astype(bool)), (i, se, wb, we)
+
+
+def test_live_ranges_rejects_bad_arguments():
+    L = B.lib()
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    assert L.loza_ssa_live_ranges(-1, 0, 1, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == ERR_SHAPE
+    assert L.loza_ssa_live_ranges(0, -1, 1, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == ERR_SHAPE
+    assert L.loza_ssa_live_ranges(0, 0, 0, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == ERR_SHAPE
+    assert L.loza_ssa_live_ranges(0, 0, 1, None, ctypes.byref(b), ctypes.byref(c)) == ERR_NULL
+
+
+@pytest.mark.parametrize("S,n_sink,window", [(1, 0, 1), (700, 4, 8), (700, 0, INF), (1024, 64, 256), (700, 300, 5),
+                                             (32768, 128, 4096), (20000, 128, 8192)])
+def test_live_pairs_match_oracle_count(S, n_sink, window):
+    w = window if window != INF else oracle.INT64_MAX
+    assert B.loza_ssa_live_pairs(S, n_sink, window) == oracle.count_pairs(S, n_sink, w)
+
+
+def test_live_pairs_closed_form_of_the_headline_shape():
+    # T = n_sink + window keys once the sequence is longer than that: T(T+1)/2 + (S - T) T
+    S, T = 131072, 128 + 8192
+    assert B.loza_ssa_live_pairs(S, 128, 8192) == T * (T + 1) // 2 + (S - T) * T
+
+
+# ---- argument validation: every case returns before the first HIP call --------------------------
+
+FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first
+
+
+def _prefill(fn="loza_ssa_prefill", q=FAKE, k=FAKE, v=FAKE, out=FAKE, lse=FAKE, B_=1, Hq=64, Hkv=1, S=256,
+             d_qk=None, d_v=None, n_sink=128, window=64, scale=0.07):
+    if d_qk is None:  # a shape the entry point has a kernel for
+        d_qk, d_v = (576, 512) if fn == "loza_ssa_prefill" else (64, 64)
+    return getattr(B.lib(), fn)(q, k, v, out, lse, B_, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale, None)
+
+
+@pytest.mark.parametrize("fn", ["loza_ssa_prefill", "loza_ssa_prefill_f32"])
+def test_prefill_rejects_null_and_misaligned(fn):
+    for name in ("q", "k", "v", "out", "lse"):
+        assert _prefill(fn, **{name: None}) == ERR_NULL, name
+    for name in ("q", "out"):
+        assert _prefill(fn, **{name: FAKE + 2}) == ERR_ALIGN, name
+    assert _prefill(fn, k=FAKE + 2, v=FAKE + 2) == ERR_ALIGN
+
+
+@pytest.mark.parametrize("fn", ["loza_ssa_prefill", "loza_ssa_prefill_f32"])
+def test_prefill_rejects_bad_sizes(fn):
+    assert _prefill(fn, B_=0) == ERR_SHAPE
+    assert _prefill(fn, S=0) == ERR_SHAPE
+    assert _prefill(fn, Hq=6, Hkv=4) == ERR_SHAPE
+    assert _prefill(fn, n_sink=-1) == ERR_SHAPE
+    assert _prefill(fn, window=0) == ERR_SHAPE
+    assert _prefill(fn, scale=float("nan")) == ERR_SHAPE
+    assert _prefill(fn, scale=float("inf")) == ERR_SHAPE
+    assert _prefill(fn, S=1 << 31) == ERR_SHAPE
+
+
+def test_bf16_prefill_rejects_non_positive_scale_and_unbuilt_shapes():
+    assert _prefill(scale=0.0) == ERR_SHAPE
+    assert _prefill(scale=-0.1) == ERR_SHAPE
+    assert _prefill(d_qk=96, d_v=96, v=FAKE + 64) == ERR_UNSUPPORTED
+    assert _prefill(d_qk=576, d_v=512, v=FAKE + 64) == ERR_UNSUPPORTED  # the MLA shape needs v == k
+    assert _prefill(d_qk=64, d_v=128) == ERR_SHAPE                      # v == k needs d_v <= d_qk
+
+
+def test_f32_prefill_rejects_wide_heads():
+    assert _prefill("loza_ssa_prefill_f32", d_qk=257, d_v=64, v=FAKE + 64) == ERR_UNSUPPORTED
+
+
+def _decode(q=FAKE, kc=FAKE, vc=FAKE, sl=FAKE, out=FAKE, lse=FAKE, B_=4, Hq=64, Hkv=1, S_max=4096, d_qk=576, d_v=512,
+            n_sink=128, window=1024, scale=0.07, ws=FAKE, ws_bytes=None):
+    if ws_bytes is None:
+        ws_bytes = B.loza_ssa_decode_workspace_bytes(B_, Hq, Hkv, S_max, d_v, n_sink, window)
+    return B.lib().loza_ssa_decode(q, kc, vc, sl, out, lse, B_, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, scale,
+                                   ws, ws_bytes, None)
+
+
+def test_decode_rejects_bad_arguments():
+    for name in ("q", "kc", "vc", "sl", "out", "lse"):
+        assert _decode(**{name: None}) == ERR_NULL, name
+    assert _decode(ws=None) == ERR_WORKSPACE
+    assert _decode(ws_bytes=15) == ERR_WORKSPACE
+    assert _decode(q=FAKE + 4) == ERR_ALIGN
+    assert _decode(window=0) == ERR_SHAPE
+    assert _decode(scale=0.0) == ERR_SHAPE
+    assert _decode(Hq=65, Hkv=2) == ERR_SHAPE
+    assert _decode(d_qk=80, d_v=80, vc=FAKE + 64) == ERR_UNSUPPORTED
+
+
+def test_decode_split_count_and_workspace_size():
+    # enough splits to give each of the 256 compute units a workgroup, never more than key tiles
+    assert B.loza_ssa_decode_num_splits(64, 64, 1, 262144, 128, 8192) == 4
+    assert B.loza_ssa_decode_num_splits(256, 64, 1, 262144, 128, 8192) == 1
+    assert B.loza_ssa_decode_num_splits(1, 64, 1, 64, 0, 64) <= 3
+    n = B.loza_ssa_decode_num_splits(3, 32, 4, 10000, 16, 512)
+    assert 1 <= n <= 64
+    # per (b, query head, split): d_v fp32 of partial output and four floats of softmax state
+    assert B.loza_ssa_decode_workspace_bytes(3, 32, 4, 10000, 128, 16, 512) == 3 * 32 * n * (128 + 4) * 4
+    assert B.loza_ssa_decode_workspace_bytes(0, 32, 4, 10000, 128, 16, 512) == 0
+    assert B.loza_ssa_decode_num_splits(3, 32, 5, 10000, 16, 512) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
+    with pytest.raises(FileNotFoundError):
+        B.lib()
