@@ -242,6 +242,22 @@ def test_decode_row_is_last_prefill_row_of_a_longer_cache():
     np.testing.assert_allclose(out_c, ref[0, i], atol=1e-12)
 
 
+def test_disjoint_key_sets_combine_by_the_log_sum_exp_rule():
+    # attention over A u B (disjoint) from attention over A and over B: lse = ln(e^lA + e^lB),
+    # out = e^(lA - lse) outA + e^(lB - lse) outB. This identity is what a key-split decode merges
+    # with; here it is checked on the oracle itself, the parts being two caches cut from one.
+    L, m, d, dv, Hq = 37, 14, 8, 6, 2
+    q, cache, vcache = _rand((Hq, d), 70), _rand((1, L, 1, d), 71), _rand((1, L, 1, dv), 72)
+    kw = dict(Hq=Hq, n_sink=0, window=oracle.INT64_MAX, scale=0.4)
+    full, lse = oracle.ssa_rows(q, cache, vcache, [0, 0], [0, 1], [L - 1, L - 1], **kw)
+    oa, la = oracle.ssa_rows(q, cache[:, :m].contiguous(), vcache[:, :m].contiguous(), [0, 0], [0, 1], [m - 1] * 2, **kw)
+    ob, lb = oracle.ssa_rows(q, cache[:, m:].contiguous(), vcache[:, m:].contiguous(), [0, 0], [0, 1], [L - m - 1] * 2, **kw)
+    merged_lse = np.logaddexp(la, lb)
+    merged = np.exp(la - merged_lse)[:, None] * oa + np.exp(lb - merged_lse)[:, None] * ob
+    np.testing.assert_allclose(merged_lse, lse, atol=1e-12)
+    np.testing.assert_allclose(merged, full, atol=1e-12)
+
+
 def test_bad_arguments_are_rejected():
     q, k, v = _rand((1, 4, 1, 4), 1), _rand((1, 4, 1, 4), 2), _rand((1, 4, 1, 4), 3)
     with pytest.raises(RuntimeError):
