@@ -196,14 +196,6 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const int i_max = DECODE ? (int)(L - 1) : (int)(((r0 + M - 1 < R) ? r0 + M - 1 : R - 1) / G);
 
     bf16x8 qf[DQK / 16];
-    {
-        const int hh = DECODE ? (int)my_row_c : (int)(my_row_c - (int64_t)i_row * G);
-        const int64_t qrow = DECODE ? ((int64_t)b * p.Hq + (int64_t)g * G + hh)
-                                    : (((int64_t)b * p.S + i_row) * p.Hq + (int64_t)g * G + hh);
-        const uint16_t *qp = p.q + qrow * DQK + lh * 8;
-#pragma unroll
-        for (int kk = 0; kk < DQK / 16; ++kk) qf[kk] = *(const bf16x8 *)(qp + kk * 16);
-    }
 
     // ---- live key tiles: sink tiles [0, nA), then window tiles [wt0, wt0 + nB) -------------------
     const int sink_end = n_sink < i_max + 1 ? n_sink : i_max + 1;
@@ -399,8 +391,8 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
     // The softmax as a list of micro-jobs, one or a few of which are issued after each matrix
     // instruction of the value phase: 0 mask + maximum of scores 0..7, 1 maximum of 8..15, 2 other
-    // wavefront half + scale, 3 reference update, then per pair of scores i: 4+3i exponentials,
-    // 5+3i bf16 pack + pair sum, 6+3i running sums; last the hand-over through LDS. The empty asm
+    // wavefront half + scale, 3 reference update, then per pair of scores i: 4+3i and 5+3i one
+    // exponential each, 6+3i bf16 pack + running sums; last the hand-over through LDS. The empty asm
     // statements anchor each job's results in its slot (the optimiser otherwise sinks all of this
     // arithmetic below the last matrix instruction).
     constexpr int SM_JOBS = 4 + 3 * 8 + 1;
@@ -424,9 +416,11 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             if (part == 0) {
                 // exp2(scale*log2(e)*s - m): a dead key (s = -inf) gives exactly 0
                 s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], p.scale_log2, -sm_m_use));
-                s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
                 asm volatile("" : "+v"(s));
             } else if (part == 1) {
+                s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
+                asm volatile("" : "+v"(s));
+            } else {
                 sm_pk[i] = pack_bf16(s[e], s[e + 1]);
                 if (PRECISE) {
                     // second bf16 term of each weight: what the first rounding lost
@@ -434,14 +428,11 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                     sm_pk_lo[i] = pack_bf16(s[e] - h0, s[e + 1] - h1);
                     asm volatile("" : "+v"(sm_pk_lo[i]));
                 }
-                s[e] += s[e + 1];  // the pair sum takes the place of the first value
-                asm volatile("" : "+v"(s), "+v"(sm_pk[i]));
-            } else {
-                sm_psum += s[e];
+                sm_psum += s[e] + s[e + 1];
                 // the sum of the two rounded values, by one dot product with (1, 1)
                 sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[i]), ones, sm_rsum, false);
                 if (PRECISE) sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[i]), ones, sm_rsum, false);
-                asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum));
+                asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum), "+v"(sm_pk[i]));
             }
         } else if (j == SM_JOBS - 1) {
             sm_end_fn(pbuf);
@@ -565,6 +556,17 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 #pragma unroll
         for (int a = 0; a < AHEAD; ++a)
             if (a < nt) issue_tile(t_begin + a, a, 0);
+        // The query fragments are requested after the first key tiles, so that both first-touch
+        // latencies run together; the score phase waits for them (and with them for every copy
+        // issued so far) through the compiler's own wait count.
+        if (scorer) {
+            const int hh = DECODE ? (int)my_row_c : (int)(my_row_c - (int64_t)i_row * G);
+            const int64_t qrow = DECODE ? ((int64_t)b * p.Hq + (int64_t)g * G + hh)
+                                        : (((int64_t)b * p.S + i_row) * p.Hq + (int64_t)g * G + hh);
+            const uint16_t *qp = p.q + qrow * DQK + lh * 8;
+#pragma unroll
+            for (int kk = 0; kk < DQK / 16; ++kk) qf[kk] = *(const bf16x8 *)(qp + kk * 16);
+        }
         // tile 0 has landed when at most the copies of the later ones are outstanding
         if (nt >= AHEAD) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 1) * C::MIN_COPIES));
         else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
