@@ -43,6 +43,13 @@ def _load():
         lib.oracle_ssa_live_mask.argtypes = [i64, i64, i64, i64, vp]
         lib.oracle_ssa_count_pairs.restype = i64
         lib.oracle_ssa_count_pairs.argtypes = [i64, i64, i64]
+        lib.oracle_ssa_rows_blocks.restype = ci
+        lib.oracle_ssa_rows_blocks.argtypes = [vp, vp, vp, ci, i64, vp, vp, vp, ci, ci, ci, i64, ci, ci,
+                                               i64, i64, i64, i64, i64, ctypes.c_double, vp, vp, vp, ci]
+        lib.oracle_ssa_live_mask_blocks.restype = ci
+        lib.oracle_ssa_live_mask_blocks.argtypes = [i64, i64, i64, i64, i64, vp]
+        lib.oracle_ssa_count_pairs_blocks.restype = i64
+        lib.oracle_ssa_count_pairs_blocks.argtypes = [i64, i64, i64, i64]
         _lib = lib
     return _lib
 
@@ -76,8 +83,12 @@ def _dtype_code(a: np.ndarray) -> int:
 
 
 def ssa_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, n_sink, window, scale,
-             want_weights=False, n_threads=None):
+             want_weights=False, n_threads=None, block=None):
     """SSA (Eq. 4) for the listed query rows.
+
+    ``block=None``: token-granular pattern, ``n_sink`` and ``window`` in tokens. ``block=b``: the
+    paper's block-granular pattern, ``n_sink`` = number of sink blocks, ``window`` = number of local
+    blocks (the query's own block counted), blocks of ``b`` tokens.
 
     q_rows [n, d_qk]; k [B, S, Hkv, d_qk]; v [B, S, Hkv, d_v], or ``v=("alias", d_v)`` when the
     values are the first ``d_v`` columns of the key rows (absorbed MLA: one latent serves both).
@@ -103,12 +114,14 @@ def ssa_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, n_sink, window, scale,
     lse = np.empty((n,), dtype=np.float64)
     w = np.zeros((n, S), dtype=np.float64) if want_weights else None
     window = min(int(window), INT64_MAX)
-    rc = lib.oracle_ssa_rows(
-        qa.ctypes.data, ka.ctypes.data, va.ctypes.data, _dtype_code(qa), n,
-        rb.ctypes.data, rh.ctypes.data, ri.ctypes.data, B, int(Hq), Hkv, S, d_qk, d_v,
-        k_stride, v_stride, int(n_sink), window, float(scale),
-        out.ctypes.data, lse.ctypes.data, w.ctypes.data if w is not None else None,
-        int(n_threads or host_threads()))
+    head = (qa.ctypes.data, ka.ctypes.data, va.ctypes.data, _dtype_code(qa), n,
+            rb.ctypes.data, rh.ctypes.data, ri.ctypes.data, B, int(Hq), Hkv, S, d_qk, d_v, k_stride, v_stride)
+    tail = (float(scale), out.ctypes.data, lse.ctypes.data, w.ctypes.data if w is not None else None,
+            int(n_threads or host_threads()))
+    if block is None:
+        rc = lib.oracle_ssa_rows(*head, int(n_sink), window, *tail)
+    else:
+        rc = lib.oracle_ssa_rows_blocks(*head, int(n_sink), window, int(block), *tail)
     if rc != 0:
         raise RuntimeError(f"oracle_ssa_rows failed with code {rc}")
     return (out, lse, w) if want_weights else (out, lse)
@@ -127,3 +140,19 @@ def live_mask(i, S, n_sink, window) -> np.ndarray:
 def count_pairs(S, n_sink, window) -> int:
     """Live (query, key) pairs of a length-S causal prefill, counted one by one."""
     return int(_load().oracle_ssa_count_pairs(int(S), int(n_sink), min(int(window), INT64_MAX)))
+
+
+def live_mask_blocks(i, S, sink_blocks, local_blocks, block) -> np.ndarray:
+    """0/1 vector over keys 0..S-1: which keys query i sees under the block-granular pattern."""
+    m = np.zeros((S,), dtype=np.uint8)
+    rc = _load().oracle_ssa_live_mask_blocks(int(i), int(S), int(sink_blocks), min(int(local_blocks), INT64_MAX),
+                                             int(block), m.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_ssa_live_mask_blocks failed with code {rc}")
+    return m
+
+
+def count_pairs_blocks(S, sink_blocks, local_blocks, block) -> int:
+    """Live (query, key) pairs of a length-S causal prefill under the block-granular pattern."""
+    return int(_load().oracle_ssa_count_pairs_blocks(int(S), int(sink_blocks), min(int(local_blocks), INT64_MAX),
+                                                     int(block)))

@@ -18,7 +18,10 @@
  * (1 sink block + 7 local blocks of 128 = 1,024 live tokens, Training section), reduction to
  * textbook causal attention for window >= S (Eq. 2 -> Eq. 1) checked against an independent
  * library routine, closed forms for Q = 0 / constant V / single-key rows, shift invariance of
- * the scores, grouped-head mapping, and brute-force masks built from Python sets.
+ * the scores, grouped-head mapping, and brute-force masks built from Python sets.  The
+ * block-granular pattern is pinned by the paper's printed sizes (block 128, 1 sink block, 7 local
+ * blocks: at most 1,024 live tokens), hand-enumerated live sets, its block = 1 case (which is the
+ * token-granular pattern) and the same library routine under a mask built from Python sets.
  */
 #include <math.h>
 #include <pthread.h>
@@ -41,6 +44,20 @@ static int alive(int64_t i, int64_t j, int64_t n_sink, int64_t window)
     return 0;
 }
 
+/* The same pattern as the paper parametrises it (Architecture section, after Eq. 4; values in the
+ * Training section): keys and queries are cut into blocks of `block` tokens, and the query in
+ * block floor(i / block) sees the first `sink_blocks` key blocks and the `local_blocks` most recent
+ * key blocks, its own block counted and cut at the query itself (causal).  With block = 1 this is
+ * alive() with n_sink = sink_blocks and window = local_blocks. */
+static int alive_blocks(int64_t i, int64_t j, int64_t sink_blocks, int64_t local_blocks, int64_t block)
+{
+    if (j > i) return 0;
+    const int64_t qb = i / block, kb = j / block;
+    if (kb < sink_blocks) return 1;
+    if (qb - kb < local_blocks) return 1;
+    return 0;
+}
+
 /* bf16 is the upper half of an IEEE fp32: widening is exact. */
 static double widen(const void *base, int dtype, int64_t idx)
 {
@@ -60,7 +77,8 @@ typedef struct {
     int64_t S;
     int d_qk, d_v;
     int64_t k_row_stride, v_row_stride; /* elements between consecutive (position, kv-head) rows */
-    int64_t n_sink, window;
+    int64_t n_sink, window; /* tokens; or sink blocks and local blocks when block > 0 */
+    int64_t block;          /* 0: token-granular pattern; > 0: block-granular with this block size */
     double scale;
     double *out, *lse, *weights;
     int64_t next_row; /* shared work counter */
@@ -78,7 +96,9 @@ static int one_row(job_t *J, int64_t r, double *score /* S doubles */)
     double m = -INFINITY;
 
     for (int64_t j = 0; j < S; ++j) {
-        if (!alive(i, j, J->n_sink, J->window)) { score[j] = -INFINITY; continue; }
+        const int live = J->block > 0 ? alive_blocks(i, j, J->n_sink, J->window, J->block)
+                                      : alive(i, j, J->n_sink, J->window);
+        if (!live) { score[j] = -INFINITY; continue; }
         const int64_t kbase = ((b * S + j) * J->Hkv + g) * J->k_row_stride;
         double dot = 0.0;
         for (int c = 0; c < J->d_qk; ++c)
@@ -134,11 +154,11 @@ static void *worker(void *arg)
  * A decode step is the row i = L - 1 of a cache whose rows j >= L are never alive (j > i).
  * Returns 0, or -1 on a bad argument, -2 if a row has no live key, -3 on allocation failure.
  */
-int oracle_ssa_rows(const void *q_rows, const void *k, const void *v, int dtype,
+static int run_rows(const void *q_rows, const void *k, const void *v, int dtype,
                     int64_t n_rows, const int64_t *row_b, const int64_t *row_h, const int64_t *row_i,
                     int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                     int64_t k_row_stride, int64_t v_row_stride,
-                    int64_t n_sink, int64_t window, double scale,
+                    int64_t n_sink, int64_t window, int64_t block, double scale,
                     double *out, double *lse, double *weights, int n_threads)
 {
     if (!q_rows || !k || !v || !out || !lse) return -1;
@@ -154,7 +174,7 @@ int oracle_ssa_rows(const void *q_rows, const void *k, const void *v, int dtype,
     J.q_rows = q_rows; J.k = k; J.v = v; J.dtype = dtype; J.n_rows = n_rows;
     J.row_b = row_b; J.row_h = row_h; J.row_i = row_i; J.Hq = Hq; J.Hkv = Hkv; J.S = S;
     J.d_qk = d_qk; J.d_v = d_v; J.k_row_stride = k_row_stride; J.v_row_stride = v_row_stride;
-    J.n_sink = n_sink; J.window = window; J.scale = scale;
+    J.n_sink = n_sink; J.window = window; J.block = block; J.scale = scale;
     J.out = out; J.lse = lse; J.weights = weights;
 
     if (n_threads < 1) n_threads = 1;
@@ -171,6 +191,31 @@ int oracle_ssa_rows(const void *q_rows, const void *k, const void *v, int dtype,
     return 0;
 }
 
+int oracle_ssa_rows(const void *q_rows, const void *k, const void *v, int dtype,
+                    int64_t n_rows, const int64_t *row_b, const int64_t *row_h, const int64_t *row_i,
+                    int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                    int64_t k_row_stride, int64_t v_row_stride,
+                    int64_t n_sink, int64_t window, double scale,
+                    double *out, double *lse, double *weights, int n_threads)
+{
+    return run_rows(q_rows, k, v, dtype, n_rows, row_b, row_h, row_i, B, Hq, Hkv, S, d_qk, d_v,
+                    k_row_stride, v_row_stride, n_sink, window, 0, scale, out, lse, weights, n_threads);
+}
+
+/* The same for the block-granular pattern: `sink_blocks` >= 0, `local_blocks` >= 1, `block` >= 1. */
+int oracle_ssa_rows_blocks(const void *q_rows, const void *k, const void *v, int dtype,
+                           int64_t n_rows, const int64_t *row_b, const int64_t *row_h, const int64_t *row_i,
+                           int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                           int64_t k_row_stride, int64_t v_row_stride,
+                           int64_t sink_blocks, int64_t local_blocks, int64_t block, double scale,
+                           double *out, double *lse, double *weights, int n_threads)
+{
+    if (block < 1) return -1;
+    return run_rows(q_rows, k, v, dtype, n_rows, row_b, row_h, row_i, B, Hq, Hkv, S, d_qk, d_v,
+                    k_row_stride, v_row_stride, sink_blocks, local_blocks, block, scale, out, lse, weights,
+                    n_threads);
+}
+
 /* The live set of one query as an explicit 0/1 vector over keys 0..S-1 (Eq. 4's pattern). */
 int oracle_ssa_live_mask(int64_t i, int64_t S, int64_t n_sink, int64_t window, uint8_t *mask)
 {
@@ -185,5 +230,23 @@ int64_t oracle_ssa_count_pairs(int64_t S, int64_t n_sink, int64_t window)
     int64_t n = 0;
     for (int64_t i = 0; i < S; ++i)
         for (int64_t j = 0; j <= i; ++j) n += alive(i, j, n_sink, window);
+    return n;
+}
+
+/* The block-granular live set of one query as a 0/1 vector over keys 0..S-1. */
+int oracle_ssa_live_mask_blocks(int64_t i, int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                uint8_t *mask)
+{
+    if (!mask || S < 1 || i < 0 || i >= S || sink_blocks < 0 || local_blocks < 1 || block < 1) return -1;
+    for (int64_t j = 0; j < S; ++j) mask[j] = (uint8_t)alive_blocks(i, j, sink_blocks, local_blocks, block);
+    return 0;
+}
+
+/* Live (query, key) pairs of a causal length-S prefill under the block-granular pattern, one by one. */
+int64_t oracle_ssa_count_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < S; ++i)
+        for (int64_t j = 0; j <= i; ++j) n += alive_blocks(i, j, sink_blocks, local_blocks, block);
     return n;
 }
