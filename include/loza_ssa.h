@@ -116,6 +116,40 @@ int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
 /* Host-only. Live (query, key) pairs of a causal length-S prefill: sum over i of |live(i)|. */
 int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window);
 
+/*
+ * The same operation under the block-granular pattern the paper parametrises SSA with
+ * (Architecture section, after Eq. 4: number of sink blocks s, number of local blocks l, block
+ * size b; Training section: b = 128, s = 1, l = 7, at most 1,024 live tokens). Keys and queries
+ * are cut into blocks of `block` tokens; the query at position i, in block qb = i / block, sees
+ *     live(i) = { j : j <= i  and ( j / block < sink_blocks  or  qb - j / block < local_blocks ) }
+ * i.e. the whole sink blocks and the local_blocks most recent blocks, its own block counted as one
+ * of them and cut at the query. |live(i)| runs through (s + l - 1) b + 1 ... (s + l) b within each
+ * block once i >= (s + l) b. With block == 1 this is the token-granular pattern with
+ * n_sink = sink_blocks and window = local_blocks.
+ * sink_blocks >= 0, local_blocks >= 1, block >= 1 (else LOZA_ERR_SHAPE); everything else
+ * (layouts, supported shapes, numerics, error behaviour) as for the token-granular twin.
+ * loza_ssa_decode_blocks takes a workspace of
+ *     loza_ssa_decode_workspace_bytes(B, Hq, Hkv, S_max, d_v, sink_blocks * block, local_blocks * block)
+ * bytes (products saturating at INT64_MAX) and uses the split count of the same sizes.
+ */
+int loza_ssa_prefill_blocks(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                            int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
+int loza_ssa_prefill_blocks_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                                int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
+int loza_ssa_decode_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                           void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                           int d_qk, int d_v, int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only twins of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern. */
+int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                int64_t *sink_end, int64_t *win_begin, int64_t *win_end);
+int64_t loza_ssa_live_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block);
+
 /* Host-only. Static string naming a status code. */
 const char *loza_status_str(int status);
 

@@ -8,4 +8,6 @@ from .binding import (  # noqa: F401
     loza_ssa_prefill, loza_ssa_prefill_f32, loza_ssa_decode,
     loza_ssa_decode_workspace_bytes, loza_ssa_decode_num_splits,
     loza_ssa_live_ranges, loza_ssa_live_pairs, loza_status_str,
+    loza_ssa_prefill_blocks, loza_ssa_prefill_blocks_f32, loza_ssa_decode_blocks,
+    loza_ssa_live_ranges_blocks, loza_ssa_live_pairs_blocks,
 )

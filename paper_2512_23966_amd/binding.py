@@ -24,6 +24,8 @@ EXPORTS = (
     "loza_ssa_prefill", "loza_ssa_prefill_f32", "loza_ssa_decode",
     "loza_ssa_decode_workspace_bytes", "loza_ssa_decode_num_splits",
     "loza_ssa_live_ranges", "loza_ssa_live_pairs", "loza_status_str",
+    "loza_ssa_prefill_blocks", "loza_ssa_prefill_blocks_f32", "loza_ssa_decode_blocks",
+    "loza_ssa_live_ranges_blocks", "loza_ssa_live_pairs_blocks",
 )
 
 
@@ -56,6 +58,16 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_live_ranges.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.loza_ssa_live_pairs.restype = i64
         L.loza_ssa_live_pairs.argtypes = [i64, i64, i64]
+        L.loza_ssa_prefill_blocks.restype = ci
+        L.loza_ssa_prefill_blocks.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp]
+        L.loza_ssa_prefill_blocks_f32.restype = ci
+        L.loza_ssa_prefill_blocks_f32.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp]
+        L.loza_ssa_decode_blocks.restype = ci
+        L.loza_ssa_decode_blocks.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_live_ranges_blocks.restype = ci
+        L.loza_ssa_live_ranges_blocks.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.loza_ssa_live_pairs_blocks.restype = i64
+        L.loza_ssa_live_pairs_blocks.argtypes = [i64, i64, i64, i64]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -99,7 +111,7 @@ def loza_ssa_live_pairs(S: int, n_sink: int, window) -> int:
     return int(lib().loza_ssa_live_pairs(int(S), int(n_sink), _win(window)))
 
 
-def _prefill_common(fn_name, dtype, q, k, v, out, lse, n_sink, window, scale, stream):
+def _prefill_common(fn_name, dtype, q, k, v, out, lse, pattern, scale, stream):
     B, S, Hq, d_qk = q.shape
     Hkv = k.shape[2]
     d_v = out.shape[3]
@@ -110,7 +122,7 @@ def _prefill_common(fn_name, dtype, q, k, v, out, lse, n_sink, window, scale, st
     qp, kp = _dev_ptr(q, dtype, "q"), _dev_ptr(k, dtype, "k")
     vp = kp if v is k else _dev_ptr(v, dtype, "v")
     rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(out, dtype, "out"), _dev_ptr(lse, torch.float32, "lse"),
-                                 B, Hq, Hkv, S, d_qk, d_v, int(n_sink), _win(window), float(scale), _stream(stream))
+                                 B, Hq, Hkv, S, d_qk, d_v, *pattern, float(scale), _stream(stream))
     if rc != LOZA_OK:
         raise LozaError(rc, fn_name)
 
@@ -119,12 +131,38 @@ def loza_ssa_prefill(q, k, v, out, lse, n_sink, window, scale, stream=None):
     """bf16 SSA prefill. q [B,S,Hq,d_qk], k [B,S,Hkv,d_qk], v [B,S,Hkv,d_v] or ``v is k`` (absorbed
     MLA: values are the first d_v columns of k), out [B,S,Hq,d_v] bf16, lse [B,Hq,S] fp32.
     ``window=None`` means infinity (full causal attention)."""
-    _prefill_common("loza_ssa_prefill", torch.bfloat16, q, k, v, out, lse, n_sink, window, scale, stream)
+    _prefill_common("loza_ssa_prefill", torch.bfloat16, q, k, v, out, lse, (int(n_sink), _win(window)), scale, stream)
 
 
 def loza_ssa_prefill_f32(q, k, v, out, lse, n_sink, window, scale, stream=None):
     """fp32 twin of :func:`loza_ssa_prefill`."""
-    _prefill_common("loza_ssa_prefill_f32", torch.float32, q, k, v, out, lse, n_sink, window, scale, stream)
+    _prefill_common("loza_ssa_prefill_f32", torch.float32, q, k, v, out, lse, (int(n_sink), _win(window)), scale, stream)
+
+
+def loza_ssa_prefill_blocks(q, k, v, out, lse, sink_blocks, local_blocks, block, scale, stream=None):
+    """bf16 SSA prefill under the block-granular pattern (sink blocks, local blocks, block size)."""
+    _prefill_common("loza_ssa_prefill_blocks", torch.bfloat16, q, k, v, out, lse,
+                    (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
+
+
+def loza_ssa_prefill_blocks_f32(q, k, v, out, lse, sink_blocks, local_blocks, block, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_prefill_blocks`."""
+    _prefill_common("loza_ssa_prefill_blocks_f32", torch.float32, q, k, v, out, lse,
+                    (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
+
+
+def loza_ssa_live_ranges_blocks(i: int, sink_blocks: int, local_blocks, block: int):
+    """(sink_end, win_begin, win_end) of query i under the block-granular pattern. Host only."""
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = lib().loza_ssa_live_ranges_blocks(int(i), int(sink_blocks), _win(local_blocks), int(block),
+                                           ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_live_ranges_blocks")
+    return a.value, b.value, c.value
+
+
+def loza_ssa_live_pairs_blocks(S: int, sink_blocks: int, local_blocks, block: int) -> int:
+    return int(lib().loza_ssa_live_pairs_blocks(int(S), int(sink_blocks), _win(local_blocks), int(block)))
 
 
 def loza_ssa_decode_num_splits(B, Hq, Hkv, S_max, n_sink, window) -> int:
@@ -135,7 +173,7 @@ def loza_ssa_decode_workspace_bytes(B, Hq, Hkv, S_max, d_v, n_sink, window) -> i
     return int(lib().loza_ssa_decode_workspace_bytes(B, Hq, Hkv, int(S_max), d_v, int(n_sink), _win(window)))
 
 
-def loza_ssa_decode(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, workspace, stream=None):
+def _decode_common(fn_name, q, kcache, vcache, seqlens, out, lse, pattern, scale, workspace, stream):
     """bf16 SSA decode. q [B,Hq,d_qk], kcache [B,S_max,Hkv,d_qk], vcache [B,S_max,Hkv,d_v] or
     ``vcache is kcache``, seqlens [B] int32 on the GPU, out [B,Hq,d_v] bf16, lse [B,Hq] fp32,
     workspace: uint8 GPU tensor of at least ``loza_ssa_decode_workspace_bytes`` bytes."""
@@ -150,8 +188,22 @@ def loza_ssa_decode(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale,
     qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(kcache, bf, "kcache")
     vp = kp if vcache is kcache else _dev_ptr(vcache, bf, "vcache")
     wp = _dev_ptr(workspace, torch.uint8, "workspace")
-    rc = lib().loza_ssa_decode(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
-                               _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, S_max, d_qk, d_v,
-                               int(n_sink), _win(window), float(scale), wp, workspace.numel(), _stream(stream))
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                                 _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, S_max, d_qk, d_v,
+                                 *pattern, float(scale), wp, workspace.numel(), _stream(stream))
     if rc != LOZA_OK:
-        raise LozaError(rc, "loza_ssa_decode")
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_decode(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, workspace, stream=None):
+    """bf16 SSA decode (token-granular pattern); tensors as in :func:`_decode_common`."""
+    _decode_common("loza_ssa_decode", q, kcache, vcache, seqlens, out, lse, (int(n_sink), _win(window)), scale,
+                   workspace, stream)
+
+
+def loza_ssa_decode_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, local_blocks, block, scale, workspace,
+                           stream=None):
+    """bf16 SSA decode under the block-granular pattern; the workspace is sized by
+    ``loza_ssa_decode_workspace_bytes(..., sink_blocks * block, local_blocks * block)``."""
+    _decode_common("loza_ssa_decode_blocks", q, kcache, vcache, seqlens, out, lse,
+                   (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)

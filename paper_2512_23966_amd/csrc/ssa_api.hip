@@ -47,6 +47,32 @@ int decode_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t
     return (int)n;
 }
 
+// The pattern as the kernels take it: sink in tokens, window in blocks of `block` tokens, both cut
+// to what can matter for S keys. The token-granular entry points use block = 1.
+struct Pattern {
+    int n_sink, window, block;
+};
+
+inline int64_t sat_mul(int64_t a, int64_t b) { return (a != 0 && b > INT64_MAX / a) ? INT64_MAX : a * b; }
+
+Pattern token_pattern(int64_t n_sink, int64_t window, int64_t S)
+{
+    return Pattern{clamp_to(n_sink, S), clamp_to(window, S), 1};
+}
+
+// block-granular: sink_blocks >= 0, local_blocks >= 1, block >= 1 (checked by the caller)
+Pattern block_pattern(int64_t sink_blocks, int64_t local_blocks, int64_t block, int64_t S)
+{
+    const int64_t b = block < S ? block : S;  // one block already covers everything
+    if (block >= S) return Pattern{sink_blocks > 0 ? (int)S : 0, 1, (int)b};
+    return Pattern{clamp_to(sat_mul(sink_blocks, block), S), clamp_to(local_blocks, S / block + 1), (int)b};
+}
+
+int check_blocks(int64_t sink_blocks, int64_t local_blocks, int64_t block)
+{
+    return (sink_blocks < 0 || local_blocks < 1 || block < 1) ? LOZA_ERR_SHAPE : LOZA_OK;
+}
+
 void set_rescale_policy(loza::FwdParams &p)
 {
     p.exact_tiles = 8;
@@ -87,6 +113,42 @@ int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
     return LOZA_OK;
 }
 
+int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                int64_t *sink_end, int64_t *win_begin, int64_t *win_end)
+{
+    if (!sink_end || !win_begin || !win_end) return LOZA_ERR_NULL;
+    if (i < 0 || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return LOZA_ERR_SHAPE;
+    const int64_t sink_tokens = sat_mul(sink_blocks, block);
+    const int64_t se = sink_tokens < i + 1 ? sink_tokens : i + 1;
+    const int64_t qb = i / block;
+    int64_t wb = local_blocks > qb ? 0 : (qb - local_blocks + 1) * block;
+    if (wb < se) wb = se;
+    *sink_end = se;
+    *win_begin = wb;
+    *win_end = i + 1;
+    return LOZA_OK;
+}
+
+int64_t loza_ssa_live_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block)
+{
+    if (S < 1 || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return -1;
+    // query block by query block: inside one block the window start is fixed and |live(i)| grows by one
+    const int64_t sink_tokens = sat_mul(sink_blocks, block);
+    int64_t pairs = 0;
+    for (int64_t i0 = 0; i0 < S; i0 += block) {
+        const int64_t i1 = (i0 + block < S ? i0 + block : S) - 1;  // last query of the block
+        const int64_t qb = i0 / block;
+        const int64_t wb = local_blocks > qb ? 0 : (qb - local_blocks + 1) * block;
+        const int64_t n = i1 - i0 + 1;
+        if (wb <= sink_tokens) {
+            pairs += n * (i0 + 1) + n * (n - 1) / 2;                       // everything up to the query
+        } else {
+            pairs += n * (sink_tokens + i0 + 1 - wb) + n * (n - 1) / 2;    // sink + [wb, i]
+        }
+    }
+    return pairs;
+}
+
 int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
 {
     if (S < 1 || n_sink < 0 || window < 1) return -1;
@@ -95,12 +157,13 @@ int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
     return T * (T + 1) / 2 + (S - T) * T;
 }
 
-int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
-                     int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
-                     int64_t n_sink, int64_t window, float scale, void *stream)
+static int prefill_bf16(const void *q, const void *k, const void *v, void *out, float *lse,
+                        int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                        int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream)
 {
     if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
-    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale)) return rc;
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     if (!(scale > 0.f)) return LOZA_ERR_SHAPE;  // the row maximum is taken before the scaling
     const bool alias = (v == k);
     if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
@@ -115,19 +178,35 @@ int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, flo
     p.q = (const uint16_t *)q; p.k = (const uint16_t *)k; p.v = (const uint16_t *)v;
     p.out = (uint16_t *)out; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S;
-    p.n_sink = clamp_to(n_sink, S); p.window = clamp_to(window, S);
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S) : token_pattern(sink, local, S);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
     p.scale_log2 = scale * 1.44269504088896340736f;
     p.row_tiles = (int)row_tiles; p.n_splits = 1;
     set_rescale_policy(p);
     return loza::launch_prefill_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 
-int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
-                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
-                         int64_t n_sink, int64_t window, float scale, void *stream)
+int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                     int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    return prefill_bf16(q, k, v, out, lse, B, Hq, Hkv, S, d_qk, d_v, n_sink, window, 1, false, scale, stream);
+}
+
+int loza_ssa_prefill_blocks(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                            int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    return prefill_bf16(q, k, v, out, lse, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true, scale, stream);
+}
+
+static int prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                       int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                       int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream)
 {
     if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
-    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale)) return rc;
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     const bool alias = (v == k);
     if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
     if (d_qk > 256 || d_v > 256) return LOZA_ERR_UNSUPPORTED;
@@ -138,9 +217,24 @@ int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *
     p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.d_qk = d_qk; p.d_v = d_v;
     p.k_row = d_qk; p.v_row = alias ? d_qk : d_v;
-    p.n_sink = clamp_to(n_sink, S); p.window = clamp_to(window, S);
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S) : token_pattern(sink, local, S);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
     p.scale = scale;
     return loza::launch_prefill_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                         int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    return prefill_f32(q, k, v, out, lse, B, Hq, Hkv, S, d_qk, d_v, n_sink, window, 1, false, scale, stream);
+}
+
+int loza_ssa_prefill_blocks_f32(const float *q, const float *k, const float *v, float *out, float *lse,
+                                int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    return prefill_f32(q, k, v, out, lse, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true, scale, stream);
 }
 
 int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window)
@@ -158,14 +252,17 @@ size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, in
     return (size_t)B * Hq * n * ((size_t)d_v + 4) * sizeof(float);
 }
 
-int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
-                    void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
-                    int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
-                    void *workspace, size_t workspace_bytes, void *stream)
+static int decode_bf16(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                       void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                       int d_qk, int d_v, int64_t sink, int64_t local, int64_t block, bool blocks, float scale,
+                       void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
-    if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, scale)) return rc;
+    if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     if (!(scale > 0.f)) return LOZA_ERR_SHAPE;
+    // the split count and the workspace are sized by the token counts the pattern can reach
+    const int64_t n_sink = blocks ? sat_mul(sink, block) : sink, window = blocks ? sat_mul(local, block) : local;
     const bool alias = (vcache == kcache);
     if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
     if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;
@@ -187,11 +284,30 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
     p.part_ml = (float *)workspace + (size_t)B * Hq * n_splits * d_v;
     p.seqlens = seqlens;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S_max;
-    p.n_sink = clamp_to(n_sink, S_max); p.window = clamp_to(window, S_max);
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S_max) : token_pattern(sink, local, S_max);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
     p.scale_log2 = scale * 1.44269504088896340736f;
     p.row_tiles = (int)row_tiles; p.n_splits = n_splits;
     set_rescale_policy(p);
     return loza::launch_decode_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                    void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                    int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return decode_bf16(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false,
+                       scale, workspace, workspace_bytes, stream);
+}
+
+int loza_ssa_decode_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                           void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                           int d_qk, int d_v, int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    return decode_bf16(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, sink_blocks, local_blocks,
+                       block, true, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -143,6 +143,19 @@ struct TileCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
+// First key of the window of query i: the window holds the `window` most recent blocks of `block`
+// tokens, the query's own block included (block = 1: the `window` most recent tokens).
+__device__ __forceinline__ int window_begin_of(int i, int window, int block)
+{
+    const int qb = block == 1 ? i : i / block;
+    return window > qb ? 0 : (qb - window + 1) * block;
+}
+
+// A decode query with fewer live keys than this is not worth a matrix-core pass and, with so few
+// terms, would show the bf16 rounding of the softmax weights in its output: the split kernel leaves
+// it alone and the merge kernel computes it directly in fp32.
+constexpr int kDirectKeys = 128;
+
 template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
@@ -172,20 +185,16 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const int64_t L = DECODE ? ((int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S) : p.S;
     const int64_t R = DECODE ? (int64_t)G : p.S * (int64_t)G;    // query rows of this (b, g)
     const int64_t r0 = (int64_t)rt * M;
-    const int n_sink = p.n_sink, window = p.window;
+    const int n_sink = p.n_sink;
+    const int window = p.window, block = p.block;
+    auto window_begin = [&](int i) { return window_begin_of(i, window, block); };
 
-    // ---- decode of an empty cache: a neutral partial ------------------------------------------
-    if (DECODE && L <= 0) {
-        for (int r = tid; r < M; r += 64 * NW) {
-            if (r0 + r >= R) continue;
-            const int64_t h = (int64_t)b * p.Hq + (int64_t)g * G + r0 + r;
-            float *po = p.part_o + (h * p.n_splits + split) * DV;
-            for (int c = 0; c < DV; ++c) po[c] = 0.f;
-            p.part_ml[(h * p.n_splits + split) * 4 + 0] = LOZA_NEG_INF;
-            p.part_ml[(h * p.n_splits + split) * 4 + 1] = 0.f;
-            p.part_ml[(h * p.n_splits + split) * 4 + 2] = 0.f;
-        }
-        return;
+    // ---- decode queries with a handful of live keys (or none) belong to the merge kernel ------
+    if (DECODE) {
+        const int64_t se = n_sink < L ? n_sink : L;
+        const int64_t wb = L > 0 ? window_begin_of((int)(L - 1), p.window, p.block) : 0;
+        const int64_t n_live = se + (L - (wb > se ? wb : se));
+        if (n_live < kDirectKeys) return;
     }
 
     // ---- the query row this lane scores ---------------------------------------------------------
@@ -199,7 +208,8 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 
     // ---- live key tiles: sink tiles [0, nA), then window tiles [wt0, wt0 + nB) -------------------
     const int sink_end = n_sink < i_max + 1 ? n_sink : i_max + 1;
-    const int win_begin = window > i_min ? 0 : i_min - window + 1;
+    const int win_begin = window_begin(i_min);
+    const int w_lo_row = window_begin(i_row), w_lo_max = window_begin(i_max);
     int nA = (sink_end + N - 1) / N;
     const int wt0 = win_begin / N, wt1 = i_max / N;
     int nB;
@@ -343,13 +353,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     auto sm_mask = [&](f32x16 &s, const int j0) {
         // tiles the pattern cuts: causal diagonal, trailing edge of the window, end of the sink
         // (j0 + N - 1 cannot overflow: j0 <= 0x3fffffff, the "no such tile" marker, masks everything)
-        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (i_max - j0 < window));
+        const bool interior = (j0 + N - 1 <= i_min) && ((j0 + N - 1 < n_sink) || (j0 >= w_lo_max));
         if (!interior) {
             const int jb = j0 + 4 * lh;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int j = jb + 8 * (e >> 2) + (e & 3);
-                const bool ok = (j <= i_row) & ((j < n_sink) | (i_row - j < window));
+                const bool ok = (j <= i_row) & ((j < n_sink) | (j >= w_lo_row));
                 s[e] = ok ? s[e] : LOZA_NEG_INF;
             }
         }
@@ -715,38 +725,93 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 // sum r_s of the same values as rounded to bf16 (what O_s was accumulated from):
 //   m* = max_s m_s ;  w_s = 2^(m_s - m*) ;  out = sum_s w_s O_s / sum_s w_s r_s ;
 //   lse = (m* + log2 sum_s w_s l_s) ln 2.
-template <int DV>
-__global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const float *__restrict__ part_o,
-                                                                   const float *__restrict__ part_ml,
-                                                                   uint16_t *__restrict__ out,
-                                                                   float *__restrict__ lse, int n_splits)
+// One workgroup per (sequence, query head), one thread per four output columns. A query with fewer
+// than kDirectKeys live keys never went through the split kernel: it is computed here from the
+// cache rows themselves, scores, softmax and weighted sum in fp32.
+template <int DQK, int DV>
+__global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParams p)
 {
+    constexpr int NT = DV / 4;
     const int64_t h = blockIdx.x;  // flat (b, query head)
-    const float *ml = part_ml + h * n_splits * 4;
-    float m_star = LOZA_NEG_INF;
-    for (int s = 0; s < n_splits; ++s) m_star = fmaxf(m_star, ml[4 * s]);
     const int c = threadIdx.x * 4;
-    if (m_star == LOZA_NEG_INF) {  // no live key at all (empty cache)
-        u32x2 z; z[0] = 0; z[1] = 0;
-        *(u32x2 *)(out + h * DV + c) = z;
-        if (threadIdx.x == 0) lse[h] = LOZA_NEG_INF;
+    const int n_splits = p.n_splits;
+    uint16_t *out = p.out + h * DV + c;
+
+    // ---- few live keys: the whole query here, in fp32 (the split kernel skipped it) --------------
+    const int b = (int)(h / p.Hq), hq = (int)(h - (int64_t)b * p.Hq), g = hq / p.G;
+    const int64_t L = (int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S;
+    const int64_t se = p.n_sink < L ? p.n_sink : L;
+    int64_t wb = L > 0 ? window_begin_of((int)(L - 1), p.window, p.block) : 0;
+    if (wb < se) wb = se;
+    const int64_t n_live = se + (L - wb);
+    if (n_live < kDirectKeys) {
+        if (n_live <= 0) {  // empty cache
+            u32x2 z; z[0] = 0; z[1] = 0;
+            *(u32x2 *)out = z;
+            if (threadIdx.x == 0) p.lse[h] = LOZA_NEG_INF;
+            return;
+        }
+        __shared__ float s_w[kDirectKeys];
+        const int n = (int)n_live;
+        const uint16_t *q = p.q + h * DQK;
+        const int64_t k_step = (int64_t)p.Hkv * DQK;
+        const bool alias = (p.v == p.k);
+        const int64_t v_step = (int64_t)p.Hkv * (alias ? DQK : DV);
+        const uint16_t *kb = p.k + ((int64_t)b * p.S * p.Hkv + g) * DQK;
+        const uint16_t *vb = p.v + ((int64_t)b * p.S * p.Hkv + g) * (alias ? DQK : DV);
+        auto key_of = [&](int t) { return t < se ? (int64_t)t : wb + (t - se); };
+        auto widen = [](uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); };
+        for (int t = threadIdx.x; t < n; t += NT) {
+            const uint16_t *kr = kb + key_of(t) * k_step;
+            float dot = 0.f;
+            for (int e = 0; e < DQK; ++e) dot = __builtin_fmaf(widen(q[e]), widen(kr[e]), dot);
+            s_w[t] = dot * p.scale_log2;
+        }
+        __syncthreads();
+        float m = LOZA_NEG_INF;
+        for (int t = 0; t < n; ++t) m = fmaxf(m, s_w[t]);
+        __syncthreads();
+        for (int t = threadIdx.x; t < n; t += NT) s_w[t] = __builtin_amdgcn_exp2f(s_w[t] - m);
+        __syncthreads();
+        float l = 0.f;
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < n; ++t) {
+            const float w = s_w[t];
+            const uint16_t *vr = vb + key_of(t) * v_step + c;
+            l += w;
+            acc.x = __builtin_fmaf(w, widen(vr[0]), acc.x);
+            acc.y = __builtin_fmaf(w, widen(vr[1]), acc.y);
+            acc.z = __builtin_fmaf(w, widen(vr[2]), acc.z);
+            acc.w = __builtin_fmaf(w, widen(vr[3]), acc.w);
+        }
+        const float inv = 1.0f / l;
+        u32x2 w2;
+        w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
+        w2[1] = pack_bf16(acc.z * inv, acc.w * inv);
+        *(u32x2 *)out = w2;
+        if (threadIdx.x == 0) p.lse[h] = (m + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f;
         return;
     }
+
+    // ---- merge of the key splits -------------------------------------------------------------------
+    const float *ml = p.part_ml + h * n_splits * 4;
+    float m_star = LOZA_NEG_INF;
+    for (int s = 0; s < n_splits; ++s) m_star = fmaxf(m_star, ml[4 * s]);
     float den = 0.f, den_r = 0.f;
     float4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < n_splits; ++s) {
         const float w = __builtin_amdgcn_exp2f(ml[4 * s] - m_star);
         den += w * ml[4 * s + 1];
         den_r += w * ml[4 * s + 2];
-        const float4 v = *(const float4 *)(part_o + (h * n_splits + s) * DV + c);
+        const float4 v = *(const float4 *)(p.part_o + (h * n_splits + s) * DV + c);
         acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
     }
     const float inv = 1.0f / den_r;
     u32x2 w2;
     w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
     w2[1] = pack_bf16(acc.z * inv, acc.w * inv);
-    *(u32x2 *)(out + h * DV + c) = w2;
-    if (threadIdx.x == 0) lse[h] = (m_star + __builtin_amdgcn_logf(den)) * 0.69314718055994530942f;
+    *(u32x2 *)out = w2;
+    if (threadIdx.x == 0) p.lse[h] = (m_star + __builtin_amdgcn_logf(den)) * 0.69314718055994530942f;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -775,7 +840,9 @@ static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
 {
     const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
     int n_prec = (int)((prec_rows + 127) / 128);
-    if (n_prec > p.row_tiles) n_prec = p.row_tiles;
+    // a pattern whose rows never reach that many live keys takes the two-term variant throughout
+    const int64_t min_live = (int64_t)p.n_sink + (int64_t)(p.window - 1) * p.block + 1;
+    if (n_prec > p.row_tiles || min_live < kPrecisePositions) n_prec = p.row_tiles;
     // the long tiles first: the short precise ones fill the tail
     hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false>(p, n_prec, p.row_tiles - n_prec, stream);
     if (e != hipSuccess) return e;
@@ -793,8 +860,7 @@ static hipError_t launch_decode_t(const FwdParams &p, hipStream_t stream)
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ssa_decode_merge_kernel<DV>, dim3((unsigned)((int64_t)p.B * p.Hq)), dim3(DV / 4), 0, stream,
-                       p.part_o, p.part_ml, p.out, p.lse, p.n_splits);
+    hipLaunchKernelGGL((ssa_decode_merge_kernel<DQK, DV>), dim3((unsigned)((int64_t)p.B * p.Hq)), dim3(DV / 4), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -36,7 +36,8 @@ __global__ __launch_bounds__(64 * F32_WAVES) void ssa_prefill_f32_kernel(const F
 
     // live keys: [0, se) then [wb, i], disjoint and ordered
     const int se = p.n_sink < i + 1 ? p.n_sink : i + 1;
-    int wb = p.window > i ? 0 : i - p.window + 1;
+    const int qblk = i / p.block;
+    int wb = p.window > qblk ? 0 : (qblk - p.window + 1) * p.block;
     if (wb < se) wb = se;
     const int n_live = se + (i - wb + 1);
 

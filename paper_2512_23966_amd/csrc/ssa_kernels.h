@@ -8,8 +8,11 @@
 namespace loza {
 
 // Arguments of the bf16 forward kernels. `S` is the sequence length of a prefill, or the row
-// count (stride) of each sequence's cache in a decode. n_sink and window are already cut to
-// [0, S] by the host (a window of S keys or more is "infinite").
+// count (stride) of each sequence's cache in a decode. The live set of query i is
+//   { j <= i : j < n_sink  or  j >= max(0, i / block - window + 1) * block },
+// n_sink in tokens, window in blocks of `block` tokens (block = 1: the token-granular pattern, the
+// window then counts tokens). n_sink and window are already cut by the host to what can matter
+// for S keys (a window that covers S keys or more is "infinite").
 struct FwdParams {
     const uint16_t *q, *k, *v;
     uint16_t *out;
@@ -19,7 +22,7 @@ struct FwdParams {
     const int32_t *seqlens;
     int B, Hq, Hkv, G;
     int64_t S;
-    int n_sink, window;
+    int n_sink, window, block;
     float scale_log2;  // scale * log2(e)
     int row_tiles;     // workgroup tiles per (batch, kv head) in this launch
     int rt_begin;      // first of them
@@ -41,7 +44,7 @@ struct F32Params {
     int64_t S;
     int d_qk, d_v;
     int64_t k_row, v_row;  // elements per key / value row (v_row = d_qk when v aliases k)
-    int n_sink, window;
+    int n_sink, window, block;  // as in FwdParams
     float scale;
 };
 hipError_t launch_prefill_f32(const F32Params &p, hipStream_t stream);

@@ -77,6 +77,47 @@ def test_live_pairs_closed_form_of_the_headline_shape():
     assert B.loza_ssa_live_pairs(S, 128, 8192) == T * (T + 1) // 2 + (S - T) * T
 
 
+@pytest.mark.parametrize("s,l,b", [(1, 2, 3), (0, 1, 4), (1, 7, 128), (2, 1, 2), (1, 3, 1), (3, 2, 50), (1, 1, 1000), (0, INF, 5)])
+def test_block_live_ranges_match_oracle_mask(s, l, b):
+    S = 700
+    lo = l if l != INF else oracle.INT64_MAX
+    for i in list(range(0, 40)) + [63, 64, 127, 128, 255, 256, 257, 383, 384, 511, 512, 699]:
+        se, wb, we = B.loza_ssa_live_ranges_blocks(i, s, l, b)
+        assert 0 <= se <= wb <= we == i + 1
+        got = np.zeros(S, dtype=bool)
+        got[:se] = True
+        got[wb:we] = True
+        assert np.array_equal(got, oracle.live_mask_blocks(i, S, s, lo, b).astype(bool)), (i, se, wb, we)
+
+
+@pytest.mark.parametrize("S,s,l,b", [(1, 0, 1, 1), (700, 1, 2, 3), (700, 1, 7, 128), (1024, 1, 7, 128), (2500, 1, 7, 128),
+                                     (700, 3, 2, 50), (333, 0, 1, 1000), (700, 4, 8, 1), (5000, 2, 3, 128)])
+def test_block_live_pairs_match_oracle_count(S, s, l, b):
+    assert B.loza_ssa_live_pairs_blocks(S, s, l, b) == oracle.count_pairs_blocks(S, s, l, b)
+
+
+def test_block_size_one_is_the_token_pattern_on_the_host_too():
+    for i in (0, 5, 99, 1000):
+        assert B.loza_ssa_live_ranges_blocks(i, 7, 20, 1) == B.loza_ssa_live_ranges(i, 7, 20)
+    assert B.loza_ssa_live_pairs_blocks(4000, 7, 20, 1) == B.loza_ssa_live_pairs(4000, 7, 20)
+
+
+def test_block_entry_points_reject_bad_patterns():
+    L = B.lib()
+    a, b_, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    for s, l, b in ((-1, 1, 2), (0, 0, 2), (1, 1, 0)):
+        assert L.loza_ssa_live_ranges_blocks(3, s, l, b, ctypes.byref(a), ctypes.byref(b_), ctypes.byref(c)) == ERR_SHAPE
+        assert B.loza_ssa_live_pairs_blocks(10, s, l, b) == -1
+        assert L.loza_ssa_prefill_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 64, 1, 256, 576, 512, s, l, b, 0.07, None) == ERR_SHAPE
+        assert L.loza_ssa_prefill_blocks_f32(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 1, 256, 64, 64, s, l, b, 0.07, None) == ERR_SHAPE
+        assert L.loza_ssa_decode_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 64, 1, 4096, 576, 512, s, l, b, 0.07,
+                                        FAKE, 1 << 30, None) == ERR_SHAPE
+    assert L.loza_ssa_prefill_blocks(None, FAKE, FAKE, FAKE, FAKE, 1, 64, 1, 256, 576, 512, 1, 7, 128, 0.07, None) == ERR_NULL
+    assert L.loza_ssa_prefill_blocks(FAKE, FAKE, FAKE + 64, FAKE, FAKE, 1, 64, 1, 256, 96, 96, 1, 7, 128, 0.07, None) == ERR_UNSUPPORTED
+    assert L.loza_ssa_decode_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 64, 1, 4096, 576, 512, 1, 7, 128, 0.07,
+                                    FAKE, 15, None) == ERR_WORKSPACE
+
+
 # ---- argument validation: every case returns before the first HIP call --------------------------
 
 FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first
