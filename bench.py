@@ -176,6 +176,24 @@ def main() -> int:
             "decode_gbps": round((float(seqlens_host.sum()) * dc.d_qk * 2) / (full_decode_ms * 1e-3) / 1e9, 1),
         }
 
+    # ---- the paper's own parametrisation on the same tensors: 1 sink block + 7 local blocks of 128 ----
+    if not args.no_comparator:
+        sb, lb, blk = 1, 7, 128
+        ws_b = torch.empty(loza.loza_ssa_decode_workspace_bytes(dc.B, dc.Hq, dc.Hkv, dc.S_max, dc.d_v, sb * blk, lb * blk),
+                           dtype=torch.uint8, device=dev)
+        blk_prefill_ms = timed(lambda: loza.loza_ssa_prefill_blocks(q, k, v, out, lse, sb, lb, blk, pc.scale), 3)
+        blk_decode_ms = timed(lambda: loza.loza_ssa_decode_blocks(dq, kc, vc, seqlens, dout, dlse, sb, lb, blk, dc.scale, ws_b), 10)
+        blk_flop = 2.0 * loza.loza_ssa_live_pairs_blocks(pc.S, sb, lb, blk) * (pc.d_qk + pc.d_v) * pc.Hq * pc.B
+        blk_rows = sum(min(int(L), sb * blk + (lb - 1) * blk + (int(L) - 1) % blk + 1) for L in seqlens_host)
+        result["paper_pattern"] = {
+            "pattern": "block-granular, 1 sink block + 7 local blocks of 128 tokens (at most 1024 live tokens)",
+            "prefill_ms": round(blk_prefill_ms, 3), "prefill_tflops": round(blk_flop / (blk_prefill_ms * 1e-3) / 1e12, 1),
+            "prefill_speedup_vs_full": round(full_prefill_ms / blk_prefill_ms, 1),
+            "decode_us": round(blk_decode_ms * 1e3, 1),
+            "decode_gbps": round(blk_rows * dc.d_qk * 2 / (blk_decode_ms * 1e-3) / 1e9, 1),
+            "decode_speedup_vs_full": round(full_decode_ms / blk_decode_ms, 1),
+        }
+
     # ---- CPU oracle on a bounded sample of the same prefill workload ----------------------------------
     if not args.no_cpu_baseline:
         import oracle
