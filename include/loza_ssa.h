@@ -145,6 +145,35 @@ int loza_ssa_decode_blocks(const void *q, const void *kcache, const void *vcache
                            int d_qk, int d_v, int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * SSA decode against a PAGED KV cache (the cache layout of a serving engine; the paper's
+ * Efficiency section measures its decode kernel inside one). The rows of sequence b live in pages
+ * of `page_size` rows: logical row j is row j % page_size of physical page
+ * block_table[b * max_pages_per_seq + j / page_size].
+ *   k_pages [num_pages, page_size, Hkv, d_qk] bf16   v_pages [num_pages, page_size, Hkv, d_v] bf16
+ *           (or v_pages == k_pages: values are the first d_v elements of the key rows)
+ *   block_table [B, max_pages_per_seq] int32 (device). Only the entries of pages that hold a live
+ *           key are read (sink pages and the pages of the window); they must lie in [0, num_pages).
+ *           An entry outside that range is cut to it: no fault, but the wrong rows.
+ *   seqlens [B] int32 (device), 0 <= seqlens[b] <= max_pages_per_seq * page_size.
+ *   page_size: a power of two >= 32 (else LOZA_ERR_SHAPE).
+ *   workspace: loza_ssa_decode_workspace_bytes(B, Hq, Hkv, max_pages_per_seq * page_size, d_v, n_sink, window)
+ *           bytes (for the _blocks form with sink_blocks * block and local_blocks * block).
+ * Everything else as loza_ssa_decode / loza_ssa_decode_blocks; the result is the same bits as for
+ * the same rows in a contiguous cache.
+ */
+int loza_ssa_decode_paged(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                          const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                          int64_t num_pages, int page_size, int max_pages_per_seq, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+int loza_ssa_decode_paged_blocks(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                                 const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                                 int64_t num_pages, int page_size, int max_pages_per_seq, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host-only twins of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern. */
 int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                 int64_t *sink_end, int64_t *win_begin, int64_t *win_end);

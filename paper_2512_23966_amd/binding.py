@@ -26,6 +26,7 @@ EXPORTS = (
     "loza_ssa_live_ranges", "loza_ssa_live_pairs", "loza_status_str",
     "loza_ssa_prefill_blocks", "loza_ssa_prefill_blocks_f32", "loza_ssa_decode_blocks",
     "loza_ssa_live_ranges_blocks", "loza_ssa_live_pairs_blocks",
+    "loza_ssa_decode_paged", "loza_ssa_decode_paged_blocks",
 )
 
 
@@ -68,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_live_ranges_blocks.argtypes = [i64, i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.loza_ssa_live_pairs_blocks.restype = i64
         L.loza_ssa_live_pairs_blocks.argtypes = [i64, i64, i64, i64]
+        L.loza_ssa_decode_paged.restype = ci
+        L.loza_ssa_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_decode_paged_blocks.restype = ci
+        L.loza_ssa_decode_paged_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, i64, i64, i64, f32, vp, sz, vp]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -207,3 +212,41 @@ def loza_ssa_decode_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, lo
     ``loza_ssa_decode_workspace_bytes(..., sink_blocks * block, local_blocks * block)``."""
     _decode_common("loza_ssa_decode_blocks", q, kcache, vcache, seqlens, out, lse,
                    (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)
+
+
+def _decode_paged_common(fn_name, q, k_pages, v_pages, block_table, seqlens, out, lse, pattern, scale, workspace, stream):
+    """bf16 SSA decode against a paged cache. q [B,Hq,d_qk], k_pages [num_pages,page_size,Hkv,d_qk],
+    v_pages [num_pages,page_size,Hkv,d_v] or ``v_pages is k_pages``, block_table [B,max_pages] int32 and
+    seqlens [B] int32 on the GPU, out [B,Hq,d_v] bf16, lse [B,Hq] fp32, workspace uint8."""
+    B, Hq, d_qk = q.shape
+    num_pages, page_size, Hkv, _ = k_pages.shape
+    d_v = out.shape[2]
+    if k_pages.shape != (num_pages, page_size, Hkv, d_qk) or out.shape != (B, Hq, d_v) or lse.shape != (B, Hq) \
+            or seqlens.shape != (B,) or block_table.dim() != 2 or block_table.shape[0] != B:
+        raise ValueError("shape mismatch between q, k_pages, block_table, seqlens, out, lse")
+    if v_pages is not k_pages and v_pages.shape != (num_pages, page_size, Hkv, d_v):
+        raise ValueError("v_pages must be [num_pages, page_size, Hkv, d_v] (or the very tensor passed as k_pages)")
+    bf = torch.bfloat16
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(k_pages, bf, "k_pages")
+    vp = kp if v_pages is k_pages else _dev_ptr(v_pages, bf, "v_pages")
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(block_table, torch.int32, "block_table"),
+                                 _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                                 _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, num_pages, page_size,
+                                 block_table.shape[1], d_qk, d_v, *pattern, float(scale),
+                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_decode_paged(q, k_pages, v_pages, block_table, seqlens, out, lse, n_sink, window, scale, workspace,
+                          stream=None):
+    """Paged-cache decode, token-granular pattern; tensors as in :func:`_decode_paged_common`."""
+    _decode_paged_common("loza_ssa_decode_paged", q, k_pages, v_pages, block_table, seqlens, out, lse,
+                         (int(n_sink), _win(window)), scale, workspace, stream)
+
+
+def loza_ssa_decode_paged_blocks(q, k_pages, v_pages, block_table, seqlens, out, lse, sink_blocks, local_blocks, block,
+                                 scale, workspace, stream=None):
+    """Paged-cache decode, block-granular pattern."""
+    _decode_paged_common("loza_ssa_decode_paged_blocks", q, k_pages, v_pages, block_table, seqlens, out, lse,
+                         (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)

@@ -252,12 +252,30 @@ size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, in
     return (size_t)B * Hq * n * ((size_t)d_v + 4) * sizeof(float);
 }
 
+// Paged cache description (block_table == nullptr: contiguous cache of S_max rows per sequence).
+struct Paging {
+    const int32_t *block_table;
+    int64_t num_pages;
+    int page_size, max_pages;
+};
+
 static int decode_bf16(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                        void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
                        int d_qk, int d_v, int64_t sink, int64_t local, int64_t block, bool blocks, float scale,
-                       void *workspace, size_t workspace_bytes, void *stream)
+                       void *workspace, size_t workspace_bytes, void *stream, const Paging *paging = nullptr)
 {
     if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
+    int page_shift = 0;
+    if (paging) {
+        if (!paging->block_table) return LOZA_ERR_NULL;
+        // pages hold a power-of-two number of rows that key tiles (32 rows) divide
+        if (paging->page_size < 32 || (paging->page_size & (paging->page_size - 1)) != 0) return LOZA_ERR_SHAPE;
+        if (paging->num_pages < 1 || paging->num_pages > 2147483647LL || paging->max_pages < 1) return LOZA_ERR_SHAPE;
+        if ((int64_t)paging->max_pages * paging->page_size > kMaxSeq) return LOZA_ERR_SHAPE;
+        while ((1 << page_shift) < paging->page_size) ++page_shift;
+        S_max = (int64_t)paging->max_pages * paging->page_size;
+        if (reinterpret_cast<uintptr_t>(paging->block_table) & 3u) return LOZA_ERR_ALIGN;
+    }
     if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, sink, local, scale)) return rc;
     if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     if (!(scale > 0.f)) return LOZA_ERR_SHAPE;
@@ -283,6 +301,10 @@ static int decode_bf16(const void *q, const void *kcache, const void *vcache, co
     p.part_o = (float *)workspace;
     p.part_ml = (float *)workspace + (size_t)B * Hq * n_splits * d_v;
     p.seqlens = seqlens;
+    if (paging) {
+        p.block_table = paging->block_table;
+        p.page_shift = page_shift; p.max_pages = paging->max_pages; p.num_pages = (int)paging->num_pages;
+    }
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S_max;
     const Pattern pat = blocks ? block_pattern(sink, local, block, S_max) : token_pattern(sink, local, S_max);
     p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
@@ -299,6 +321,28 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
 {
     return decode_bf16(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false,
                        scale, workspace, workspace_bytes, stream);
+}
+
+int loza_ssa_decode_paged(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                          const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                          int64_t num_pages, int page_size, int max_pages_per_seq, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    const Paging pg{block_table, num_pages, page_size, max_pages_per_seq};
+    return decode_bf16(q, k_pages, v_pages, seqlens, out, lse, B, Hq, Hkv, 1, d_qk, d_v, n_sink, window, 1, false,
+                       scale, workspace, workspace_bytes, stream, &pg);
+}
+
+int loza_ssa_decode_paged_blocks(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                                 const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                                 int64_t num_pages, int page_size, int max_pages_per_seq, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    const Paging pg{block_table, num_pages, page_size, max_pages_per_seq};
+    return decode_bf16(q, k_pages, v_pages, seqlens, out, lse, B, Hq, Hkv, 1, d_qk, d_v, sink_blocks, local_blocks,
+                       block, true, scale, workspace, workspace_bytes, stream, &pg);
 }
 
 int loza_ssa_decode_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,

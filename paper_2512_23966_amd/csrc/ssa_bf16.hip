@@ -252,8 +252,39 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     for (int u = 0; u < C::V_PER_WAVE; ++u) vvoff[u] = copy_offset(u * NW + wave, C::VCPR, pos_stride_v);
 
     const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
-    const char *kbase = (const char *)p.k + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DQK * 2;
-    const char *vbase = (const char *)p.v + ((int64_t)b * p.S * p.Hkv + g) * (int64_t)DV * 2;
+    // A paged cache (decode only) keeps the rows of a sequence in pages of 2^page_shift rows that a
+    // block table maps to physical pages; a key tile never straddles a page (pages hold a multiple
+    // of N rows), so paging only changes where a tile starts.
+    const bool paged = DECODE && p.block_table != nullptr;
+    const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
+    const char *kbase = (const char *)p.k + (seq_row0 * p.Hkv + g) * (int64_t)DQK * 2;
+    const char *vbase = (const char *)p.v + (seq_row0 * p.Hkv + g) * (int64_t)DV * 2;
+    // The block-table entry of key tile t is fetched by a scalar load spelled out in asm (it must not
+    // count as a vector load: the tile loop waits on exact counts of those), in two steps so that
+    // the latency can be spent elsewhere: page_request() starts the load, page_wait() makes its
+    // result usable. Between the two nothing may read the value; page_wait() returns it.
+    auto page_request = [&](int t) -> int32_t {
+        int32_t pid = 0;
+        if (DECODE && paged) {
+            const int64_t j0 = (int64_t)key_tile(t) * N;
+            const int32_t *e = p.block_table + ((int64_t)b * p.max_pages + (j0 >> p.page_shift));
+            asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pid) : "s"(e) : "memory");
+        }
+        return pid;
+    };
+    auto page_wait = [&](int32_t pid) -> int32_t {
+        if (DECODE && paged) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pid) :: "memory");
+        return pid;
+    };
+    // cache row (relative to kbase / vbase) at which key tile t starts, given its block-table entry
+    auto tile_row = [&](int t, int32_t pid) -> int64_t {
+        const int64_t j0 = (int64_t)key_tile(t) * N;
+        if (DECODE && paged) {
+            pid = pid < 0 ? 0 : (pid < p.num_pages ? pid : p.num_pages - 1);  // a bad entry stays in bounds
+            return ((int64_t)pid << p.page_shift) + (j0 & ((1 << p.page_shift) - 1));
+        }
+        return j0;
+    };
 
     // One global -> LDS copy instruction: 64 lanes x 16 bytes from base + off (per lane) to the 1 KB
     // of LDS at lds_addr (wave-uniform, through M0). Spelled out in asm so that the compiler's
@@ -263,13 +294,14 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         asm volatile("s_mov_b32 m0, %2\n s_nop 0\n global_load_lds_dwordx4 %0, %1"
                      :: "v"(off), "s"(base), "s"(lds_addr) : "memory", "m0");
     };
-    // this wave's copy instructions [u_first, ...) of key tile t into `stage`
-    auto issue_tile = [&](int t, int stage, int u_first) {
+    // this wave's copy instructions [u_first, ...) of key tile t, which starts at cache row `row`,
+    // into `stage`
+    auto issue_tile = [&](int t, int stage, int u_first, int64_t row) {
         const int64_t j0 = (int64_t)key_tile(t) * N;
         // rows of the tile at or past the sequence end fetch from its last valid row instead:
         // they are dead (j > i) and only have to be finite
         const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
-        const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
+        const char *ksrc = kbase + row * (int64_t)pos_stride_k;
         const uint32_t kdst = smem_lds + stage * C::STAGE + wave * 1024;
         const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
 #pragma unroll
@@ -280,7 +312,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
         }
         if (!ALIAS) {
-            const char *vsrc = vbase + j0 * (int64_t)pos_stride_v;
+            const char *vsrc = vbase + row * (int64_t)pos_stride_v;
             const uint32_t vdst = smem_lds + stage * C::STAGE + C::KTILE + wave * 1024;
             const uint32_t vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
 #pragma unroll
@@ -319,12 +351,12 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     constexpr bool WEAVE = (DQK == 576 && ALIAS);  // copy instructions woven into the score phase
     // The same with the copy of key tile `t_copy` into stage `stage_copy` woven in (wide rows only):
     // the copy instructions issue between matrix instructions instead of ahead of them.
-    auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy) {
+    auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy, int64_t row_copy) {
         if constexpr (WEAVE) {
             const uint32_t kaddr = smem_lds + stage * C::STAGE + ln * C::KROW + lh * 16;
             const int64_t j0 = (int64_t)key_tile(t_copy) * N;
             const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
-            const char *ksrc = kbase + j0 * (int64_t)pos_stride_k;
+            const char *ksrc = kbase + row_copy * (int64_t)pos_stride_k;
             const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
             const uint32_t m0base = smem_lds + stage_copy * C::STAGE + wave * 1024;
             static_assert(!WEAVE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
@@ -565,7 +597,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     if (nt > 0) {
 #pragma unroll
         for (int a = 0; a < AHEAD; ++a)
-            if (a < nt) issue_tile(t_begin + a, a, 0);
+            if (a < nt) issue_tile(t_begin + a, a, 0, tile_row(t_begin + a, page_wait(page_request(t_begin + a))));
         // The query fragments are requested after the first key tiles, so that both first-touch
         // latencies run together; the score phase waits for them (and with them for every copy
         // issued so far) through the compiler's own wait count.
@@ -594,10 +626,16 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         lds_barrier();  // ... everyone's; P of tile u is visible; the stage of tile u - 1 is free
     };
     constexpr int WOVEN = LOZA_SCORE_COPIES_576_W4;
+    // where the tile issued in iteration u starts: looked up one iteration ahead (a paged cache
+    // reads its block table here, and the answer is there when the copies are issued)
+    auto tile_ahead = [&](int u) { return t_begin + u + AHEAD < t_end ? t_begin + u + AHEAD : t_end - 1; };
+    int32_t page_pre = nt > 0 ? page_request(tile_ahead(0)) : 0;
     if (!SPEC) {
         int st_v = 0;  // ring stage of tile u
         for (int u = 0; u < nt; ++u) {
             top_of_tile(u);
+            const int64_t row_now = tile_row(tile_ahead(u), page_wait(page_pre));
+            page_pre = page_request(tile_ahead(u + 1));
             const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
             const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;  // = (u + AHEAD) % NSTAGE
             const bool more = u + AHEAD < nt;
@@ -606,10 +644,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             value_prefetch(st_v, u & 1, vf);
             __builtin_amdgcn_sched_barrier(0);
             if (WEAVE && more) {
-                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l);
-                issue_tile(t_begin + u + AHEAD, st_l, WOVEN);  // what was not woven in
+                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l, row_now);
+                issue_tile(t_begin + u + AHEAD, st_l, WOVEN, row_now);  // what was not woven in
             } else {
-                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0);
+                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0, row_now);
                 score_tile(st_k, s);
             }
             rescale_tile(u & 1, flags);
@@ -623,14 +661,16 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         int st_v = 0;
         for (int u = 0; u < nt; ++u) {
             top_of_tile(u);
+            const int64_t row_now = tile_row(tile_ahead(u), page_wait(page_pre));
+            page_pre = page_request(tile_ahead(u + 1));
             const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
             const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
             const bool more = u + AHEAD < nt;
             if (WEAVE && more) {
-                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l);
-                issue_tile(t_begin + u + AHEAD, st_l, WOVEN);
+                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l, row_now);
+                issue_tile(t_begin + u + AHEAD, st_l, WOVEN, row_now);
             } else {
-                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0);
+                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0, row_now);
                 score_tile(st_k, s);
             }
             softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
@@ -642,11 +682,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         int st_v = 0;
         for (int u = 0; u < nt; ++u) {
             top_of_tile(u);
+            const int64_t row_now = tile_row(tile_ahead(u), page_wait(page_pre));
+            page_pre = page_request(tile_ahead(u + 1));
             const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
             const u32x4 flags = rescale_flags(u & 1);
             ValueFrags vf;
             value_prefetch(st_v, u & 1, vf);
-            if (u + AHEAD < nt) issue_tile(t_begin + u + AHEAD, st_l, 0);
+            if (u + AHEAD < nt) issue_tile(t_begin + u + AHEAD, st_l, 0, row_now);
             rescale_tile(u & 1, flags);
             value_tile(st_v, u & 1, vf, std::false_type{}, s, 0, 0, 0.f);
             st_v = st_v + 1 < NSTAGE ? st_v + 1 : 0;
@@ -757,9 +799,18 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParam
         const int64_t k_step = (int64_t)p.Hkv * DQK;
         const bool alias = (p.v == p.k);
         const int64_t v_step = (int64_t)p.Hkv * (alias ? DQK : DV);
-        const uint16_t *kb = p.k + ((int64_t)b * p.S * p.Hkv + g) * DQK;
-        const uint16_t *vb = p.v + ((int64_t)b * p.S * p.Hkv + g) * (alias ? DQK : DV);
-        auto key_of = [&](int t) { return t < se ? (int64_t)t : wb + (t - se); };
+        const bool paged = p.block_table != nullptr;
+        const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
+        const uint16_t *kb = p.k + (seq_row0 * p.Hkv + g) * DQK;
+        const uint16_t *vb = p.v + (seq_row0 * p.Hkv + g) * (alias ? DQK : DV);
+        // cache row of the t-th live key (through the block table of a paged cache)
+        auto key_of = [&](int t) {
+            const int64_t j = t < se ? (int64_t)t : wb + (t - se);
+            if (!paged) return j;
+            int pid = p.block_table[(int64_t)b * p.max_pages + (j >> p.page_shift)];
+            pid = pid < 0 ? 0 : (pid < p.num_pages ? pid : p.num_pages - 1);
+            return ((int64_t)pid << p.page_shift) + (j & ((1 << p.page_shift) - 1));
+        };
         auto widen = [](uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); };
         for (int t = threadIdx.x; t < n; t += NT) {
             const uint16_t *kr = kb + key_of(t) * k_step;

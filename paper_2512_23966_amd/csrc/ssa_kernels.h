@@ -20,6 +20,10 @@ struct FwdParams {
     float *part_o;   // decode: [B, Hq, n_splits, d_v] unnormalised partial outputs
     float *part_ml;  // decode: [B, Hq, n_splits, 4]   reference max (log2 domain), sum, rounded sum, pad
     const int32_t *seqlens;
+    // paged decode cache (else nullptr): logical page j >> page_shift of sequence b is physical page
+    // block_table[b * max_pages + (j >> page_shift)] of k / v, which are then [num_pages, 2^page_shift, Hkv, d]
+    const int32_t *block_table;
+    int page_shift, max_pages, num_pages;
     int B, Hq, Hkv, G;
     int64_t S;
     int n_sink, window, block;

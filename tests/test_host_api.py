@@ -118,6 +118,30 @@ def test_block_entry_points_reject_bad_patterns():
                                     FAKE, 15, None) == ERR_WORKSPACE
 
 
+def _paged(page_size=128, num_pages=100, max_pages=8, table=None, ws_bytes=1 << 30, **kw):
+    args = dict(B_=2, Hq=64, Hkv=1, d_qk=576, d_v=512, n_sink=128, window=256, scale=0.07)
+    args.update(kw)
+    return B.lib().loza_ssa_decode_paged(FAKE, FAKE, FAKE, FAKE if table is None else table, FAKE, FAKE, FAKE,
+                                         args["B_"], args["Hq"], args["Hkv"], num_pages, page_size, max_pages,
+                                         args["d_qk"], args["d_v"], args["n_sink"], args["window"], args["scale"],
+                                         FAKE, ws_bytes, None)
+
+
+def test_paged_decode_rejects_bad_paging():
+    assert _paged(page_size=96) == ERR_SHAPE      # not a power of two
+    assert _paged(page_size=16) == ERR_SHAPE      # smaller than a key tile
+    assert _paged(num_pages=0) == ERR_SHAPE
+    assert _paged(max_pages=0) == ERR_SHAPE
+    assert _paged(max_pages=1 << 30) == ERR_SHAPE  # capacity beyond the supported sequence length
+    assert _paged(ws_bytes=15) == ERR_WORKSPACE
+    assert _paged(window=0) == ERR_SHAPE
+    assert _paged(d_qk=80, d_v=80) == ERR_UNSUPPORTED
+    assert B.lib().loza_ssa_decode_paged(FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 2, 64, 1, 100, 128, 8, 576, 512,
+                                         128, 256, 0.07, FAKE, 1 << 30, None) == ERR_NULL
+    assert B.lib().loza_ssa_decode_paged_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 64, 1, 100, 128, 8, 576, 512,
+                                                1, 0, 128, 0.07, FAKE, 1 << 30, None) == ERR_SHAPE
+
+
 # ---- argument validation: every case returns before the first HIP call --------------------------
 
 FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first
