@@ -174,6 +174,29 @@ int loza_ssa_decode_paged_blocks(const void *q, const void *k_pages, const void 
                                  int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Calibration forward (paper: Architecture section, Eq. 3): the layer output with the learnable
+ * mixing factor alpha in [0, 1] between full attention O and streaming sparse attention O',
+ *     out = alpha * O + (1 - alpha) * O'
+ * for the block-granular pattern (block == 1: token-granular with n_sink = sink_blocks and
+ * window = local_blocks). Two prefill passes (all causal keys; the sparse pattern) leave their
+ * unrounded fp32 outputs in the workspace; a third kernel mixes them and rounds once to bf16.
+ *   out        [B, S, Hq, d_v] bf16  the blend
+ *   out_full   NULL or [B, S, Hq, d_v] bf16: O itself      out_sparse  NULL or the same for O'
+ *              (alpha's gradient is the inner product of the incoming gradient with O - O')
+ *   lse_full, lse_sparse [B, Hq, S] fp32: the log-sum-exp of either pass
+ *   workspace  loza_ssa_calibration_workspace_bytes(B, Hq, S, d_v) bytes, 16-byte aligned
+ * alpha outside [0, 1] or NaN: LOZA_ERR_SHAPE. Everything else as loza_ssa_prefill_blocks.
+ */
+int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void *v,
+                                        void *out, void *out_full, void *out_sparse, float *lse_full, float *lse_sparse,
+                                        int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                        int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                        float alpha, float scale, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only. Workspace bytes of loza_ssa_prefill_calibration_blocks (0 on invalid sizes). */
+size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v);
+
 /* Host-only twins of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern. */
 int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                 int64_t *sink_end, int64_t *win_begin, int64_t *win_end);

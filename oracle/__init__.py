@@ -156,3 +156,16 @@ def count_pairs_blocks(S, sink_blocks, local_blocks, block) -> int:
     """Live (query, key) pairs of a length-S causal prefill under the block-granular pattern."""
     return int(_load().oracle_ssa_count_pairs_blocks(int(S), int(sink_blocks), min(int(local_blocks), INT64_MAX),
                                                      int(block)))
+
+
+def calibration_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, sink_blocks, local_blocks, block, alpha, scale,
+                     n_threads=None):
+    """Calibration forward of the paper (Architecture section, Eq. 3) for the listed rows:
+    ``alpha * O + (1 - alpha) * O'`` with O the full causal attention output and O' the streaming
+    sparse one (block-granular pattern). Returns (blend, o_full, o_sparse, lse_full, lse_sparse)."""
+    o_full, lse_full = ssa_rows(q_rows, k, v, row_b, row_h, row_i, Hq=Hq, n_sink=0, window=INT64_MAX, scale=scale,
+                                n_threads=n_threads)
+    o_sparse, lse_sparse = ssa_rows(q_rows, k, v, row_b, row_h, row_i, Hq=Hq, n_sink=sink_blocks, window=local_blocks,
+                                    block=block, scale=scale, n_threads=n_threads)
+    a = float(alpha)
+    return a * o_full + (1.0 - a) * o_sparse, o_full, o_sparse, lse_full, lse_sparse

@@ -27,6 +27,7 @@ EXPORTS = (
     "loza_ssa_prefill_blocks", "loza_ssa_prefill_blocks_f32", "loza_ssa_decode_blocks",
     "loza_ssa_live_ranges_blocks", "loza_ssa_live_pairs_blocks",
     "loza_ssa_decode_paged", "loza_ssa_decode_paged_blocks",
+    "loza_ssa_prefill_calibration_blocks", "loza_ssa_calibration_workspace_bytes",
 )
 
 
@@ -73,6 +74,11 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_decode_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, i64, i64, f32, vp, sz, vp]
         L.loza_ssa_decode_paged_blocks.restype = ci
         L.loza_ssa_decode_paged_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_prefill_calibration_blocks.restype = ci
+        L.loza_ssa_prefill_calibration_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci,
+                                                          i64, i64, i64, f32, f32, vp, sz, vp]
+        L.loza_ssa_calibration_workspace_bytes.restype = sz
+        L.loza_ssa_calibration_workspace_bytes.argtypes = [ci, ci, i64, ci]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -250,3 +256,35 @@ def loza_ssa_decode_paged_blocks(q, k_pages, v_pages, block_table, seqlens, out,
     """Paged-cache decode, block-granular pattern."""
     _decode_paged_common("loza_ssa_decode_paged_blocks", q, k_pages, v_pages, block_table, seqlens, out, lse,
                          (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)
+
+
+def loza_ssa_calibration_workspace_bytes(B, Hq, S, d_v) -> int:
+    return int(lib().loza_ssa_calibration_workspace_bytes(B, Hq, int(S), d_v))
+
+
+def loza_ssa_prefill_calibration_blocks(q, k, v, out, out_full, out_sparse, lse_full, lse_sparse,
+                                        sink_blocks, local_blocks, block, alpha, scale, workspace, stream=None):
+    """Calibration forward: out = alpha * O_full + (1 - alpha) * O_sparse (bf16). ``out_full`` / ``out_sparse``
+    may be None; lse_full, lse_sparse [B,Hq,S] fp32; workspace uint8 of ``loza_ssa_calibration_workspace_bytes``."""
+    B, S, Hq, d_qk = q.shape
+    Hkv = k.shape[2]
+    d_v = out.shape[3]
+    bf = torch.bfloat16
+    if k.shape != (B, S, Hkv, d_qk) or out.shape != (B, S, Hq, d_v) or lse_full.shape != (B, Hq, S) or lse_sparse.shape != (B, Hq, S):
+        raise ValueError("shape mismatch between q, k, out, lse_full, lse_sparse")
+    for t in (out_full, out_sparse):
+        if t is not None and t.shape != out.shape:
+            raise ValueError("out_full / out_sparse must have the shape of out")
+    if v is not k and v.shape != (B, S, Hkv, d_v):
+        raise ValueError("v must be [B, S, Hkv, d_v] (or the very tensor passed as k)")
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(k, bf, "k")
+    vp = kp if v is k else _dev_ptr(v, bf, "v")
+    rc = lib().loza_ssa_prefill_calibration_blocks(
+        qp, kp, vp, _dev_ptr(out, bf, "out"),
+        None if out_full is None else _dev_ptr(out_full, bf, "out_full"),
+        None if out_sparse is None else _dev_ptr(out_sparse, bf, "out_sparse"),
+        _dev_ptr(lse_full, torch.float32, "lse_full"), _dev_ptr(lse_sparse, torch.float32, "lse_sparse"),
+        B, Hq, Hkv, S, d_qk, d_v, int(sink_blocks), _win(local_blocks), int(block), float(alpha), float(scale),
+        _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_prefill_calibration_blocks")

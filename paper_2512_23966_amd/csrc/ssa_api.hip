@@ -159,9 +159,10 @@ int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
 
 static int prefill_bf16(const void *q, const void *k, const void *v, void *out, float *lse,
                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
-                        int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream)
+                        int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream,
+                        float *out_f32 = nullptr, bool validate_only = false)
 {
-    if (!q || !k || !v || !out || !lse) return LOZA_ERR_NULL;
+    if (!q || !k || !v || (!out && !out_f32) || !lse) return LOZA_ERR_NULL;
     if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
     if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     if (!(scale > 0.f)) return LOZA_ERR_SHAPE;  // the row maximum is taken before the scaling
@@ -173,10 +174,11 @@ static int prefill_bf16(const void *q, const void *k, const void *v, void *out, 
     const int rows = loza::prefill_rows_per_tile();
     const int64_t row_tiles = (S * G + rows - 1) / rows;
     if (row_tiles * Hkv * B > 2147483647LL) return LOZA_ERR_SHAPE;
+    if (validate_only) return LOZA_OK;
 
     loza::FwdParams p{};
     p.q = (const uint16_t *)q; p.k = (const uint16_t *)k; p.v = (const uint16_t *)v;
-    p.out = (uint16_t *)out; p.lse = lse;
+    p.out = (uint16_t *)out; p.out_f32 = out_f32; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.S = S;
     const Pattern pat = blocks ? block_pattern(sink, local, block, S) : token_pattern(sink, local, S);
     p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
@@ -221,6 +223,43 @@ static int prefill_f32(const float *q, const float *k, const float *v, float *ou
     p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
     p.scale = scale;
     return loza::launch_prefill_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v)
+{
+    if (B < 1 || Hq < 1 || S < 1 || d_v < 1 || S > kMaxSeq) return 0;
+    return (size_t)2 * B * S * Hq * d_v * sizeof(float);
+}
+
+int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void *v,
+                                        void *out, void *out_full, void *out_sparse, float *lse_full, float *lse_sparse,
+                                        int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                        int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                        float alpha, float scale, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out || !lse_full || !lse_sparse) return LOZA_ERR_NULL;
+    if (!(alpha >= 0.f && alpha <= 1.f)) return LOZA_ERR_SHAPE;
+    const size_t need = loza_ssa_calibration_workspace_bytes(B, Hq, S, d_v);
+    if (need == 0) return LOZA_ERR_SHAPE;
+    if (!workspace || workspace_bytes < need) return LOZA_ERR_WORKSPACE;
+    if (!aligned16(out) || !aligned16(workspace) || (out_full && !aligned16(out_full)) || (out_sparse && !aligned16(out_sparse)))
+        return LOZA_ERR_ALIGN;
+    float *o_full = (float *)workspace, *o_sparse = o_full + need / (2 * sizeof(float));
+    // every argument of both passes is checked before the first launch
+    if (int rc = prefill_bf16(q, k, v, nullptr, lse_full, B, Hq, Hkv, S, d_qk, d_v, 0, 1, INT64_MAX, true, scale, stream, o_full, true))
+        return rc;
+    if (int rc = prefill_bf16(q, k, v, nullptr, lse_sparse, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                              scale, stream, o_sparse, true))
+        return rc;
+    // O: every causal key (one block that holds everything); O': the sparse pattern
+    if (int rc = prefill_bf16(q, k, v, nullptr, lse_full, B, Hq, Hkv, S, d_qk, d_v, 0, 1, INT64_MAX, true, scale, stream, o_full))
+        return rc;
+    if (int rc = prefill_bf16(q, k, v, nullptr, lse_sparse, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                              scale, stream, o_sparse))
+        return rc;
+    const int64_t n = (int64_t)B * S * Hq * d_v;  // a multiple of 8: d_v is
+    return loza::launch_blend_bf16(o_full, o_sparse, alpha, (uint16_t *)out, (uint16_t *)out_full, (uint16_t *)out_sparse, n,
+                                   (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 
 int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,

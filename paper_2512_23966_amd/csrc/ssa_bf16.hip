@@ -156,7 +156,7 @@ __device__ __forceinline__ int window_begin_of(int i, int window, int block)
 // it alone and the merge kernel computes it directly in fp32.
 constexpr int kDirectKeys = 128;
 
-template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false>
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false, bool OUTF32 = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
     using C = TileCfg<DQK, DV, RB, ALIAS, DECODE, PRECISE>;
@@ -720,16 +720,33 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             if (row < R) {
                 const int64_t i = row / G;
                 const int hh = (int)(row - i * G);
-                uint16_t *op = p.out + ((((int64_t)b * p.S + i) * p.Hq + (int64_t)g * G + hh) * DV) + vw * C::DVW + 4 * lh;
+                const int64_t o_idx = ((((int64_t)b * p.S + i) * p.Hq + (int64_t)g * G + hh) * DV) + vw * C::DVW + 4 * lh;
+                if constexpr (OUTF32) {
+                    // unrounded output (the calibration blend rounds once, after mixing two of these)
+                    float *op = p.out_f32 + o_idx;
 #pragma unroll
-                for (int db = 0; db < C::DVB; ++db)
+                    for (int db = 0; db < C::DVB; ++db)
 #pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        u32x2 w;
-                        w[0] = pack_bf16(o[db][rb][4 * qd + 0] * inv, o[db][rb][4 * qd + 1] * inv);
-                        w[1] = pack_bf16(o[db][rb][4 * qd + 2] * inv, o[db][rb][4 * qd + 3] * inv);
-                        *(u32x2 *)(op + db * 32 + qd * 8) = w;
-                    }
+                        for (int qd = 0; qd < 4; ++qd) {
+                            float4 w;
+                            w.x = o[db][rb][4 * qd + 0] * inv;
+                            w.y = o[db][rb][4 * qd + 1] * inv;
+                            w.z = o[db][rb][4 * qd + 2] * inv;
+                            w.w = o[db][rb][4 * qd + 3] * inv;
+                            *(float4 *)(op + db * 32 + qd * 8) = w;
+                        }
+                } else {
+                    uint16_t *op = p.out + o_idx;
+#pragma unroll
+                    for (int db = 0; db < C::DVB; ++db)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            u32x2 w;
+                            w[0] = pack_bf16(o[db][rb][4 * qd + 0] * inv, o[db][rb][4 * qd + 1] * inv);
+                            w[1] = pack_bf16(o[db][rb][4 * qd + 2] * inv, o[db][rb][4 * qd + 3] * inv);
+                            *(u32x2 *)(op + db * 32 + qd * 8) = w;
+                        }
+                }
             }
         }
     } else {
@@ -871,12 +888,12 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParam
 // of the error budget there. Beyond it every output averages enough keys for that to vanish.
 constexpr int kPrecisePositions = 128;
 
-template <int DQK, int DV, bool ALIAS, bool PRECISE>
+template <int DQK, int DV, bool ALIAS, bool PRECISE, bool OUTF32>
 static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
 {
     if (rt_count <= 0) return hipSuccess;
     using C = TileCfg<DQK, DV, 4, ALIAS, false, PRECISE>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE>;
+    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE, OUTF32>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     p.rt_begin = rt_begin;
@@ -891,13 +908,33 @@ static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
 {
     const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
     int n_prec = (int)((prec_rows + 127) / 128);
-    // a pattern whose rows never reach that many live keys takes the two-term variant throughout
-    const int64_t min_live = (int64_t)p.n_sink + (int64_t)(p.window - 1) * p.block + 1;
-    if (n_prec > p.row_tiles || min_live < kPrecisePositions) n_prec = p.row_tiles;
+    // A pattern that leaves rows beyond those positions with fewer live keys than that takes the
+    // two-term variant throughout. The smallest live set of such a row is at position
+    // kPrecisePositions - 1 or at the first query of a block whose window has reached full length.
+    auto live_at = [&](int64_t i) {
+        const int64_t se = p.n_sink < i + 1 ? p.n_sink : i + 1;
+        const int64_t qb = i / p.block;
+        int64_t wb = p.window > qb ? 0 : (qb - p.window + 1) * p.block;
+        if (wb < se) wb = se;
+        return se + (i + 1 - wb);
+    };
+    bool all_precise = false;
+    if (p.S >= kPrecisePositions) {
+        int64_t qb0 = (kPrecisePositions - 1 + p.block - 1) / p.block;
+        if (qb0 < p.window - 1) qb0 = p.window - 1;
+        const int64_t i0 = qb0 * p.block;
+        all_precise = live_at(kPrecisePositions - 1) < kPrecisePositions || (i0 < p.S && live_at(i0) < kPrecisePositions);
+    }
+    if (n_prec > p.row_tiles || all_precise) n_prec = p.row_tiles;
     // the long tiles first: the short precise ones fill the tail
-    hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false>(p, n_prec, p.row_tiles - n_prec, stream);
+    if (p.out_f32 != nullptr) {
+        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, true>(p, n_prec, p.row_tiles - n_prec, stream);
+        if (e != hipSuccess) return e;
+        return launch_prefill_part<DQK, DV, ALIAS, true, true>(p, 0, n_prec, stream);
+    }
+    hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false>(p, n_prec, p.row_tiles - n_prec, stream);
     if (e != hipSuccess) return e;
-    return launch_prefill_part<DQK, DV, ALIAS, true>(p, 0, n_prec, stream);
+    return launch_prefill_part<DQK, DV, ALIAS, true, false>(p, 0, n_prec, stream);
 }
 
 template <int DQK, int DV, bool ALIAS>
@@ -912,6 +949,37 @@ static hipError_t launch_decode_t(const FwdParams &p, hipStream_t stream)
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((ssa_decode_merge_kernel<DQK, DV>), dim3((unsigned)((int64_t)p.B * p.Hq)), dim3(DV / 4), 0, stream, p);
+    return hipGetLastError();
+}
+
+// Calibration blend (paper: Architecture section, Eq. 3): out = alpha * o_full + (1 - alpha) * o_sparse,
+// element-wise on the unrounded fp32 outputs of two prefill launches, rounded to bf16 once. The two
+// inputs can be written out rounded as well (either pointer may be null). n is a multiple of 4.
+__global__ __launch_bounds__(256) void ssa_blend_kernel(const float *__restrict__ o_full, const float *__restrict__ o_sparse,
+                                                        float alpha, uint16_t *__restrict__ out,
+                                                        uint16_t *__restrict__ out_full, uint16_t *__restrict__ out_sparse,
+                                                        int64_t n4)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        const float4 a = ((const float4 *)o_full)[i], s = ((const float4 *)o_sparse)[i];
+        const float beta = 1.0f - alpha;
+        u32x2 w;
+        w[0] = pack_bf16(__builtin_fmaf(alpha, a.x, beta * s.x), __builtin_fmaf(alpha, a.y, beta * s.y));
+        w[1] = pack_bf16(__builtin_fmaf(alpha, a.z, beta * s.z), __builtin_fmaf(alpha, a.w, beta * s.w));
+        ((u32x2 *)out)[i] = w;
+        if (out_full) { w[0] = pack_bf16(a.x, a.y); w[1] = pack_bf16(a.z, a.w); ((u32x2 *)out_full)[i] = w; }
+        if (out_sparse) { w[0] = pack_bf16(s.x, s.y); w[1] = pack_bf16(s.z, s.w); ((u32x2 *)out_sparse)[i] = w; }
+    }
+}
+
+hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float alpha, uint16_t *out,
+                             uint16_t *out_full, uint16_t *out_sparse, int64_t n, hipStream_t stream)
+{
+    const int64_t n4 = n / 4;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;  // grid-stride beyond that
+    hipLaunchKernelGGL(ssa_blend_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, o_full, o_sparse, alpha, out,
+                       out_full, out_sparse, n4);
     return hipGetLastError();
 }
 

@@ -16,6 +16,7 @@ namespace loza {
 struct FwdParams {
     const uint16_t *q, *k, *v;
     uint16_t *out;
+    float *out_f32;  // prefill only: when set, the output goes here unrounded instead of to `out`
     float *lse;
     float *part_o;   // decode: [B, Hq, n_splits, d_v] unnormalised partial outputs
     float *part_ml;  // decode: [B, Hq, n_splits, 4]   reference max (log2 domain), sum, rounded sum, pad
@@ -40,6 +41,8 @@ int prefill_rows_per_tile();
 int decode_rows_per_tile();
 hipError_t launch_prefill_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
 hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
+hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float alpha, uint16_t *out,
+                             uint16_t *out_full, uint16_t *out_sparse, int64_t n, hipStream_t stream);
 
 struct F32Params {
     const float *q, *k, *v;

@@ -142,6 +142,24 @@ def test_paged_decode_rejects_bad_paging():
                                                 1, 0, 128, 0.07, FAKE, 1 << 30, None) == ERR_SHAPE
 
 
+def test_calibration_workspace_and_validation():
+    assert B.loza_ssa_calibration_workspace_bytes(2, 64, 1000, 512) == 2 * 2 * 1000 * 64 * 512 * 4
+    assert B.loza_ssa_calibration_workspace_bytes(0, 64, 1000, 512) == 0
+
+    def call(alpha=0.5, out=FAKE, lse_f=FAKE, ws=FAKE, ws_bytes=1 << 40, s=1, l=7, b=128, d_qk=576, d_v=512, v=FAKE):
+        return B.lib().loza_ssa_prefill_calibration_blocks(FAKE, FAKE, v, out, None, None, lse_f, FAKE, 1, 64, 1, 256,
+                                                           d_qk, d_v, s, l, b, alpha, 0.07, ws, ws_bytes, None)
+    assert call(alpha=1.5) == ERR_SHAPE
+    assert call(alpha=-0.1) == ERR_SHAPE
+    assert call(alpha=float("nan")) == ERR_SHAPE
+    assert call(out=None) == ERR_NULL
+    assert call(lse_f=None) == ERR_NULL
+    assert call(ws=None) == ERR_WORKSPACE
+    assert call(ws_bytes=1000) == ERR_WORKSPACE
+    assert call(l=0) == ERR_SHAPE
+    assert call(d_qk=96, d_v=96, v=FAKE + 64) == ERR_UNSUPPORTED
+
+
 # ---- argument validation: every case returns before the first HIP call --------------------------
 
 FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first

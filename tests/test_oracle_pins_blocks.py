@@ -122,3 +122,54 @@ def test_block_arguments_are_checked():
     for s, l, b in ((0, 0, 2), (-1, 1, 2), (1, 1, 0)):
         with pytest.raises(RuntimeError):
             oracle.ssa_rows(q[0, :1, 0], k, v, [0], [0], [0], Hq=1, n_sink=s, window=l, block=b, scale=1.0)
+
+
+# ---- calibration blend (Eq. 3) -------------------------------------------------------------------
+
+def _calib_case(alpha, s=1, l=2, b=4, S=40, Hq=2, d=8, dv=5, scale=0.3):
+    q, k, v = _rand((1, S, Hq, d), 31), _rand((1, S, 1, d), 32), _rand((1, S, 1, dv), 33)
+    rb = np.zeros(S * Hq, dtype=np.int64)
+    rh = np.repeat(np.arange(Hq), S)
+    ri = np.tile(np.arange(S), Hq)
+    qr = q[0, torch.as_tensor(ri), torch.as_tensor(rh)].contiguous()
+    res = oracle.calibration_rows(qr, k, v, rb, rh, ri, Hq=Hq, sink_blocks=s, local_blocks=l, block=b, alpha=alpha,
+                                  scale=scale)
+    return (q, k, v, rh, ri), res
+
+
+def test_calibration_end_points_are_the_two_attentions():
+    _, (blend1, full, sparse, _, _) = _calib_case(1.0)
+    _, (blend0, _, _, _, _) = _calib_case(0.0)
+    np.testing.assert_array_equal(blend1, full)
+    np.testing.assert_array_equal(blend0, sparse)
+    assert np.abs(full - sparse).max() > 1e-3  # the two really differ on this input
+
+
+def test_calibration_is_the_straight_line_between_them():
+    _, (mid, full, sparse, _, _) = _calib_case(0.25)
+    np.testing.assert_allclose(mid, sparse + 0.25 * (full - sparse), atol=1e-15)
+
+
+def test_calibration_rows_that_see_their_whole_prefix_do_not_depend_on_alpha():
+    (q, k, v, rh, ri), (a, full, sparse, lf, ls) = _calib_case(0.7, s=1, l=2, b=4)
+    whole = ri < (1 + 2 - 1) * 4   # every key up to the query is in a sink or local block
+    np.testing.assert_allclose(a[whole], full[whole], atol=1e-15)
+    np.testing.assert_allclose(lf[whole], ls[whole], atol=1e-15)
+    assert np.abs(a[~whole] - full[~whole]).max() > 1e-4
+
+
+def test_calibration_against_library_attention_under_set_built_masks():
+    alpha, s, l, b, scale = 0.4, 1, 2, 4, 0.3
+    (q, k, v, rh, ri), (blend, _, _, _, _) = _calib_case(alpha, s, l, b, scale=scale)
+    S, Hq = q.shape[1], q.shape[2]
+    sparse_mask = torch.zeros(S, S, dtype=torch.bool)
+    for i in range(S):
+        for j in _set_live_blocks(i, s, l, b):
+            sparse_mask[i, j] = True
+    qd = q.double().permute(0, 2, 1, 3)
+    kd = k.double().permute(0, 2, 1, 3).repeat_interleave(Hq, dim=1)
+    vd = v.double().permute(0, 2, 1, 3).repeat_interleave(Hq, dim=1)
+    full = torch.nn.functional.scaled_dot_product_attention(qd, kd, vd, is_causal=True, scale=scale)
+    sparse = torch.nn.functional.scaled_dot_product_attention(qd, kd, vd, attn_mask=sparse_mask, scale=scale)
+    ref = (alpha * full + (1 - alpha) * sparse)[0].numpy()          # [Hq, S, dv]
+    np.testing.assert_allclose(blend.reshape(Hq, S, -1), ref, atol=1e-12)
