@@ -146,6 +146,29 @@ int loza_ssa_decode_blocks(const void *q, const void *kcache, const void *vcache
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * SSA "extend": q_len new query tokens per sequence against that sequence's KV cache, which already
+ * holds their keys and values (chunked prefill, verification of speculated tokens: the engine side of
+ * the paper's Efficiency section). Query r of sequence b sits at position seqlens[b] - q_len + r and
+ * sees the live set of that position; q_len == 1 is what loza_ssa_decode computes.
+ *   q       [B, q_len, Hq, d_qk] bf16
+ *   kcache  [B, S_max, Hkv, d_qk] bf16     vcache [B, S_max, Hkv, d_v] bf16 (or vcache == kcache)
+ *   seqlens [B] int32 (device): valid cache rows, the q_len new tokens included; a value above
+ *           S_max is cut to it. Queries whose position would be negative (seqlens[b] < q_len)
+ *           give out = 0, lse = -inf.
+ *   out     [B, q_len, Hq, d_v] bf16       lse [B, Hq, q_len] fp32
+ * 1 <= q_len <= S_max (else LOZA_ERR_SHAPE). No workspace: the prefill kernel runs over the q_len
+ * positions (no split over keys), so it suits q_len * Hq / Hkv of a few hundred rows and more.
+ * Supported shapes, numerics, errors: as loza_ssa_prefill / loza_ssa_prefill_blocks.
+ */
+int loza_ssa_extend(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens, void *out, float *lse,
+                    int B, int Hq, int Hkv, int64_t S_max, int q_len, int d_qk, int d_v,
+                    int64_t n_sink, int64_t window, float scale, void *stream);
+
+int loza_ssa_extend_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens, void *out,
+                           float *lse, int B, int Hq, int Hkv, int64_t S_max, int q_len, int d_qk, int d_v,
+                           int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
+/*
  * SSA decode against a PAGED KV cache (the cache layout of a serving engine; the paper's
  * Efficiency section measures its decode kernel inside one). The rows of sequence b live in pages
  * of `page_size` rows: logical row j is row j % page_size of physical page

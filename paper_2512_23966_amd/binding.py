@@ -28,6 +28,7 @@ EXPORTS = (
     "loza_ssa_live_ranges_blocks", "loza_ssa_live_pairs_blocks",
     "loza_ssa_decode_paged", "loza_ssa_decode_paged_blocks",
     "loza_ssa_prefill_calibration_blocks", "loza_ssa_calibration_workspace_bytes",
+    "loza_ssa_extend", "loza_ssa_extend_blocks",
 )
 
 
@@ -79,6 +80,10 @@ def lib() -> ctypes.CDLL:
                                                           i64, i64, i64, f32, f32, vp, sz, vp]
         L.loza_ssa_calibration_workspace_bytes.restype = sz
         L.loza_ssa_calibration_workspace_bytes.argtypes = [ci, ci, i64, ci]
+        L.loza_ssa_extend.restype = ci
+        L.loza_ssa_extend.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_extend_blocks.restype = ci
+        L.loza_ssa_extend_blocks.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, i64, i64, i64, f32, vp]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -288,3 +293,35 @@ def loza_ssa_prefill_calibration_blocks(q, k, v, out, out_full, out_sparse, lse_
         _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != LOZA_OK:
         raise LozaError(rc, "loza_ssa_prefill_calibration_blocks")
+
+
+def _extend_common(fn_name, q, kcache, vcache, seqlens, out, lse, pattern, scale, stream):
+    """bf16 SSA extend. q [B,q_len,Hq,d_qk], kcache [B,S_max,Hkv,d_qk], vcache [B,S_max,Hkv,d_v] or
+    ``vcache is kcache``, seqlens [B] int32 on the GPU, out [B,q_len,Hq,d_v] bf16, lse [B,Hq,q_len] fp32."""
+    B, q_len, Hq, d_qk = q.shape
+    _, S_max, Hkv, _ = kcache.shape
+    d_v = out.shape[3]
+    if kcache.shape != (B, S_max, Hkv, d_qk) or out.shape != (B, q_len, Hq, d_v) or lse.shape != (B, Hq, q_len) \
+            or seqlens.shape != (B,):
+        raise ValueError("shape mismatch between q, kcache, seqlens, out, lse")
+    if vcache is not kcache and vcache.shape != (B, S_max, Hkv, d_v):
+        raise ValueError("vcache must be [B, S_max, Hkv, d_v] (or the very tensor passed as kcache)")
+    bf = torch.bfloat16
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(kcache, bf, "kcache")
+    vp = kp if vcache is kcache else _dev_ptr(vcache, bf, "vcache")
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                                 _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, S_max, q_len, d_qk, d_v,
+                                 *pattern, float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_extend(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, stream=None):
+    """q_len new tokens per sequence against its cache, token-granular pattern (see :func:`_extend_common`)."""
+    _extend_common("loza_ssa_extend", q, kcache, vcache, seqlens, out, lse, (int(n_sink), _win(window)), scale, stream)
+
+
+def loza_ssa_extend_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, local_blocks, block, scale, stream=None):
+    """q_len new tokens per sequence against its cache, block-granular pattern."""
+    _extend_common("loza_ssa_extend_blocks", q, kcache, vcache, seqlens, out, lse,
+                   (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)

@@ -160,9 +160,13 @@ int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
 static int prefill_bf16(const void *q, const void *k, const void *v, void *out, float *lse,
                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                         int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream,
-                        float *out_f32 = nullptr, bool validate_only = false)
+                        float *out_f32 = nullptr, bool validate_only = false,
+                        const int32_t *seqlens = nullptr, int64_t q_len = 0)
 {
+    // seqlens != nullptr: "extend" form, q_len queries per sequence against a cache of S rows
+    const bool extend = seqlens != nullptr;
     if (!q || !k || !v || (!out && !out_f32) || !lse) return LOZA_ERR_NULL;
+    if (extend && (q_len < 1 || q_len > S || (reinterpret_cast<uintptr_t>(seqlens) & 3u))) return q_len < 1 || q_len > S ? LOZA_ERR_SHAPE : LOZA_ERR_ALIGN;
     if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
     if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
     if (!(scale > 0.f)) return LOZA_ERR_SHAPE;  // the row maximum is taken before the scaling
@@ -172,7 +176,7 @@ static int prefill_bf16(const void *q, const void *k, const void *v, void *out, 
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse)) return LOZA_ERR_ALIGN;
     const int G = Hq / Hkv;
     const int rows = loza::prefill_rows_per_tile();
-    const int64_t row_tiles = (S * G + rows - 1) / rows;
+    const int64_t row_tiles = ((extend ? q_len : S) * G + rows - 1) / rows;
     if (row_tiles * Hkv * B > 2147483647LL) return LOZA_ERR_SHAPE;
     if (validate_only) return LOZA_OK;
 
@@ -185,7 +189,29 @@ static int prefill_bf16(const void *q, const void *k, const void *v, void *out, 
     p.scale_log2 = scale * 1.44269504088896340736f;
     p.row_tiles = (int)row_tiles; p.n_splits = 1;
     set_rescale_policy(p);
+    if (extend) {
+        p.seqlens = seqlens; p.q_len = (int)q_len;
+        return loza::launch_extend_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+    }
     return loza::launch_prefill_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_extend(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens, void *out, float *lse,
+                    int B, int Hq, int Hkv, int64_t S_max, int q_len, int d_qk, int d_v,
+                    int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    if (!seqlens) return LOZA_ERR_NULL;
+    return prefill_bf16(q, kcache, vcache, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false, scale, stream,
+                        nullptr, false, seqlens, q_len);
+}
+
+int loza_ssa_extend_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens, void *out,
+                           float *lse, int B, int Hq, int Hkv, int64_t S_max, int q_len, int d_qk, int d_v,
+                           int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    if (!seqlens) return LOZA_ERR_NULL;
+    return prefill_bf16(q, kcache, vcache, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                        scale, stream, nullptr, false, seqlens, q_len);
 }
 
 int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,

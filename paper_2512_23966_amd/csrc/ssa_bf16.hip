@@ -151,6 +151,11 @@ __device__ __forceinline__ int window_begin_of(int i, int window, int block)
     return window > qb ? 0 : (qb - window + 1) * block;
 }
 
+// Positions below this take the two-term-P variant of the prefill kernel: with so few live keys
+// the output is as large as single value rows, and the bf16 rounding of P would be a visible share
+// of the error budget there. Beyond it every output averages enough keys for that to vanish.
+constexpr int kPrecisePositions = 128;
+
 // A decode query with fewer live keys than this is not worth a matrix-core pass and, with so few
 // terms, would show the bf16 rounding of the softmax weights in its output: the split kernel leaves
 // it alone and the merge kernel computes it directly in fp32.
@@ -181,9 +186,14 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const int b = id / p.Hkv;
     const int G = p.G;
 
-    // valid key rows (a decode length beyond the cache is cut to the cache)
-    const int64_t L = DECODE ? ((int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S) : p.S;
-    const int64_t R = DECODE ? (int64_t)G : p.S * (int64_t)G;    // query rows of this (b, g)
+    // "Extend" prefill: the last q_len positions of each sequence are the queries, the keys come
+    // from a cache whose valid length is seqlens[b] (q_len = 0: plain prefill, queries = keys = S).
+    const bool extend = !DECODE && p.q_len > 0;
+    // valid key rows (a length beyond the cache is cut to the cache)
+    const int64_t L = (DECODE || extend) ? ((int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S) : p.S;
+    const int64_t Sq = extend ? (int64_t)p.q_len : p.S;           // query positions per sequence
+    const int64_t pos0 = extend ? L - Sq : 0;                     // position of the first of them
+    const int64_t R = DECODE ? (int64_t)G : Sq * (int64_t)G;      // query rows of this (b, g)
     const int64_t r0 = (int64_t)rt * M;
     const int n_sink = p.n_sink;
     const int window = p.window, block = p.block;
@@ -200,20 +210,24 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // ---- the query row this lane scores ---------------------------------------------------------
     const int64_t my_row = r0 + wr * 32 + ln;
     const int64_t my_row_c = my_row < R ? my_row : R - 1;
-    const int i_row = DECODE ? (int)(L - 1) : (int)(my_row_c / G);
-    const int i_min = DECODE ? (int)(L - 1) : (int)(r0 / G);
-    const int i_max = DECODE ? (int)(L - 1) : (int)(((r0 + M - 1 < R) ? r0 + M - 1 : R - 1) / G);
+    const int r_row = DECODE ? 0 : (int)(my_row_c / G);           // index of the query among the Sq
+    const int i_row = DECODE ? (int)(L - 1) : (int)(pos0 + r_row);
+    const int i_min = DECODE ? (int)(L - 1) : (int)(pos0 + r0 / G);
+    const int i_max = DECODE ? (int)(L - 1) : (int)(pos0 + ((r0 + M - 1 < R) ? r0 + M - 1 : R - 1) / G);
+    // an extend launch runs both variants of the kernel over all tiles; each tile belongs to one
+    if (!DECODE && extend && !p.all_precise && ((i_min < kPrecisePositions) != PRECISE)) return;
 
     bf16x8 qf[DQK / 16];
 
     // ---- live key tiles: sink tiles [0, nA), then window tiles [wt0, wt0 + nB) -------------------
-    const int sink_end = n_sink < i_max + 1 ? n_sink : i_max + 1;
-    const int win_begin = window_begin(i_min);
+    const int sink_end = i_max < 0 ? 0 : (n_sink < i_max + 1 ? n_sink : i_max + 1);
+    const int win_begin = window_begin(i_min < 0 ? 0 : i_min);
     const int w_lo_row = window_begin(i_row), w_lo_max = window_begin(i_max);
     int nA = (sink_end + N - 1) / N;
     const int wt0 = win_begin / N, wt1 = i_max / N;
     int nB;
     if (wt0 <= nA) { nA = wt1 + 1; nB = 0; } else { nB = wt1 - wt0 + 1; }
+    if (i_max < 0) { nA = 0; nB = 0; }  // queries before the start of the sequence see nothing
     const int n_tiles = nA + nB;
     int t_begin = 0, t_end = n_tiles;
     if (DECODE) {
@@ -602,9 +616,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         // latencies run together; the score phase waits for them (and with them for every copy
         // issued so far) through the compiler's own wait count.
         if (scorer) {
-            const int hh = DECODE ? (int)my_row_c : (int)(my_row_c - (int64_t)i_row * G);
+            const int hh = DECODE ? (int)my_row_c : (int)(my_row_c - (int64_t)r_row * G);
             const int64_t qrow = DECODE ? ((int64_t)b * p.Hq + (int64_t)g * G + hh)
-                                        : (((int64_t)b * p.S + i_row) * p.Hq + (int64_t)g * G + hh);
+                                        : (((int64_t)b * Sq + r_row) * p.Hq + (int64_t)g * G + hh);
             const uint16_t *qp = p.q + qrow * DQK + lh * 8;
 #pragma unroll
             for (int kk = 0; kk < DQK / 16; ++kk) qf[kk] = *(const bf16x8 *)(qp + kk * 16);
@@ -709,18 +723,19 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     if (!DECODE) {
         // lse = ln(sum_j exp(scale q.k_j)) = (m_ref + log2 l) * ln 2
         if (scorer && lh == 0 && my_row < R) {
-            const int hh = (int)(my_row - (int64_t)i_row * G);
-            p.lse[((int64_t)b * p.Hq + (int64_t)g * G + hh) * p.S + i_row] =
+            const int hh = (int)(my_row - (int64_t)r_row * G);
+            p.lse[((int64_t)b * p.Hq + (int64_t)g * G + hh) * Sq + r_row] =
                 (m_ref + __builtin_amdgcn_logf(s_lpart[wr * 32 + ln])) * 0.69314718055994530942f;
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             const int64_t row = r0 + rb * 32 + ln;
-            const float inv = 1.0f / s_lpart[M + rb * 32 + ln];
+            const float rsum = s_lpart[M + rb * 32 + ln];
+            const float inv = rsum > 0.f ? 1.0f / rsum : 0.f;  // a row without a live key gives 0
             if (row < R) {
                 const int64_t i = row / G;
                 const int hh = (int)(row - i * G);
-                const int64_t o_idx = ((((int64_t)b * p.S + i) * p.Hq + (int64_t)g * G + hh) * DV) + vw * C::DVW + 4 * lh;
+                const int64_t o_idx = ((((int64_t)b * Sq + i) * p.Hq + (int64_t)g * G + hh) * DV) + vw * C::DVW + 4 * lh;
                 if constexpr (OUTF32) {
                     // unrounded output (the calibration blend rounds once, after mixing two of these)
                     float *op = p.out_f32 + o_idx;
@@ -883,10 +898,6 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParam
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Positions below this take the two-term-P variant of the prefill kernel: with so few live keys
-// the output is as large as single value rows, and the bf16 rounding of P would be a visible share
-// of the error budget there. Beyond it every output averages enough keys for that to vanish.
-constexpr int kPrecisePositions = 128;
 
 template <int DQK, int DV, bool ALIAS, bool PRECISE, bool OUTF32>
 static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
@@ -903,14 +914,11 @@ static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, h
     return hipGetLastError();
 }
 
-template <int DQK, int DV, bool ALIAS>
-static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
+// A pattern that leaves rows beyond the first kPrecisePositions positions with fewer live keys than
+// that takes the two-term variant throughout. The smallest live set of such a row is at position
+// kPrecisePositions - 1 or at the first query of a block whose window has reached full length.
+static bool pattern_needs_precise(const FwdParams &p)
 {
-    const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
-    int n_prec = (int)((prec_rows + 127) / 128);
-    // A pattern that leaves rows beyond those positions with fewer live keys than that takes the
-    // two-term variant throughout. The smallest live set of such a row is at position
-    // kPrecisePositions - 1 or at the first query of a block whose window has reached full length.
     auto live_at = [&](int64_t i) {
         const int64_t se = p.n_sink < i + 1 ? p.n_sink : i + 1;
         const int64_t qb = i / p.block;
@@ -918,14 +926,19 @@ static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
         if (wb < se) wb = se;
         return se + (i + 1 - wb);
     };
-    bool all_precise = false;
-    if (p.S >= kPrecisePositions) {
-        int64_t qb0 = (kPrecisePositions - 1 + p.block - 1) / p.block;
-        if (qb0 < p.window - 1) qb0 = p.window - 1;
-        const int64_t i0 = qb0 * p.block;
-        all_precise = live_at(kPrecisePositions - 1) < kPrecisePositions || (i0 < p.S && live_at(i0) < kPrecisePositions);
-    }
-    if (n_prec > p.row_tiles || all_precise) n_prec = p.row_tiles;
+    if (p.S < kPrecisePositions) return false;
+    int64_t qb0 = (kPrecisePositions - 1 + p.block - 1) / p.block;
+    if (qb0 < p.window - 1) qb0 = p.window - 1;
+    const int64_t i0 = qb0 * p.block;
+    return live_at(kPrecisePositions - 1) < kPrecisePositions || (i0 < p.S && live_at(i0) < kPrecisePositions);
+}
+
+template <int DQK, int DV, bool ALIAS>
+static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
+{
+    const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
+    int n_prec = (int)((prec_rows + 127) / 128);
+    if (n_prec > p.row_tiles || pattern_needs_precise(p)) n_prec = p.row_tiles;
     // the long tiles first: the short precise ones fill the tail
     if (p.out_f32 != nullptr) {
         hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, true>(p, n_prec, p.row_tiles - n_prec, stream);
@@ -935,6 +948,20 @@ static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
     hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false>(p, n_prec, p.row_tiles - n_prec, stream);
     if (e != hipSuccess) return e;
     return launch_prefill_part<DQK, DV, ALIAS, true, false>(p, 0, n_prec, stream);
+}
+
+// Extend prefill: which tiles lie among the first kPrecisePositions positions depends on the
+// sequence lengths on the device, so both variants run over all tiles and every tile exits from the
+// one it does not belong to.
+template <int DQK, int DV, bool ALIAS>
+static hipError_t launch_extend_t(FwdParams p, hipStream_t stream)
+{
+    p.all_precise = pattern_needs_precise(p) ? 1 : 0;
+    if (!p.all_precise) {
+        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false>(p, 0, p.row_tiles, stream);
+        if (e != hipSuccess) return e;
+    }
+    return launch_prefill_part<DQK, DV, ALIAS, true, false>(p, 0, p.row_tiles, stream);
 }
 
 template <int DQK, int DV, bool ALIAS>
@@ -998,6 +1025,14 @@ hipError_t launch_prefill_bf16(const FwdParams &p, int d_qk, int d_v, bool alias
     if (d_qk == 576 && d_v == 512 && alias) return launch_prefill_t<576, 512, true>(p, stream);
     if (d_qk == 128 && d_v == 128) return alias ? launch_prefill_t<128, 128, true>(p, stream)
                                                 : launch_prefill_t<128, 128, false>(p, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_extend_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream)
+{
+    if (d_qk == 576 && d_v == 512 && alias) return launch_extend_t<576, 512, true>(p, stream);
+    if (d_qk == 128 && d_v == 128) return alias ? launch_extend_t<128, 128, true>(p, stream)
+                                                : launch_extend_t<128, 128, false>(p, stream);
     return hipErrorInvalidValue;
 }
 

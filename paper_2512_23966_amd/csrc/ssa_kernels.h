@@ -32,6 +32,8 @@ struct FwdParams {
     int row_tiles;     // workgroup tiles per (batch, kv head) in this launch
     int rt_begin;      // first of them
     int n_splits;      // decode only
+    int q_len;         // extend prefill: queries per sequence (0: plain prefill); keys valid up to seqlens[b]
+    int all_precise;   // extend prefill: every tile takes the two-term variant
     int exact_tiles;   // tiles over which the reference maximum is the exact running maximum
     float lazy_log2;   // afterwards it moves only when exceeded by this much (log2 units)
 };
@@ -40,6 +42,7 @@ bool bf16_shape_supported(int d_qk, int d_v, bool alias);
 int prefill_rows_per_tile();
 int decode_rows_per_tile();
 hipError_t launch_prefill_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
+hipError_t launch_extend_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
 hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
 hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float alpha, uint16_t *out,
                              uint16_t *out_full, uint16_t *out_sparse, int64_t n, hipStream_t stream);

@@ -160,6 +160,19 @@ def test_calibration_workspace_and_validation():
     assert call(d_qk=96, d_v=96, v=FAKE + 64) == ERR_UNSUPPORTED
 
 
+def test_extend_rejects_bad_arguments():
+    def call(q_len=4, sl=FAKE, S_max=4096, window=256, scale=0.07, d_qk=576, d_v=512, v=FAKE):
+        return B.lib().loza_ssa_extend(FAKE, FAKE, v, sl, FAKE, FAKE, 2, 64, 1, S_max, q_len, d_qk, d_v, 128, window, scale, None)
+    assert call(q_len=0) == ERR_SHAPE
+    assert call(q_len=5000) == ERR_SHAPE      # more queries than the cache has rows
+    assert call(sl=None) == ERR_NULL
+    assert call(sl=FAKE + 2) == ERR_ALIGN
+    assert call(window=0) == ERR_SHAPE
+    assert call(scale=0.0) == ERR_SHAPE
+    assert call(d_qk=96, d_v=96, v=FAKE + 64) == ERR_UNSUPPORTED
+    assert B.lib().loza_ssa_extend_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 64, 1, 4096, 4, 576, 512, 1, 7, 0, 0.07, None) == ERR_SHAPE
+
+
 # ---- argument validation: every case returns before the first HIP call --------------------------
 
 FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first
