@@ -230,12 +230,14 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     if (i_max < 0) { nA = 0; nB = 0; }  // queries before the start of the sequence see nothing
     const int n_tiles = nA + nB;
     int t_begin = 0, t_end = n_tiles;
+    // A decode split takes every n_splits-th live tile: the splits of a sequence then walk through
+    // the same stretch of the cache together (measured a little faster than a contiguous quarter each).
+    int t_stride = 1, t_first = 0;
     if (DECODE) {
-        const int per = (n_tiles + p.n_splits - 1) / p.n_splits;
-        t_begin = split * per;
-        t_end = t_begin + per < n_tiles ? t_begin + per : n_tiles;
+        t_stride = p.n_splits; t_first = split;
+        t_end = n_tiles > split ? (n_tiles - split + p.n_splits - 1) / p.n_splits : 0;
     }
-    auto key_tile = [&](int t) { return t < nA ? t : wt0 + (t - nA); };
+    auto key_tile = [&](int t) { const int tt = t_first + t * t_stride; return tt < nA ? tt : wt0 + (tt - nA); };
 
     // ---- global -> LDS copy plan (the same for every tile) --------------------------------------
     // Copy instruction `instr` fills LDS slots [instr*64, instr*64 + 64) of the padded tile: slot p
