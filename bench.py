@@ -34,6 +34,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the untimed-region extras: the 32K MHA and the 1M-token MLA prefill configurations")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (what HBM byte counters "
                          "collected with rocprofv3 --pmc are scaled by)")
@@ -220,6 +222,48 @@ def main() -> int:
             "sample": f"{n} seeded random (position, head) rows of the 128K prefill with the full {pc.n_sink + pc.window}-key live set, "
                       f"{t_cpu:.1f} s; whole prefill would take {prefill_flop / (cpu_flop / t_cpu) / 3600:.1f} h",
         }
+
+    # ---- the other prefill configurations (outside the timed step): 32K MHA and 1M-token MLA -------------
+    if not args.no_other_configs:
+        del q, k, v, out, lse, dq, kc, vc, dout, dlse, ws
+        torch.cuda.empty_cache()
+
+        def time_prefill(cfg, reps):
+            free, _ = torch.cuda.mem_get_info()
+            need = cfg.B * cfg.S * cfg.Hq * (cfg.d_qk + cfg.d_v) * 2 * 1.1
+            if free < need:
+                return None
+            q2, k2, v2 = W.make_prefill_inputs(cfg, dev)
+            o2 = torch.empty(cfg.B, cfg.S, cfg.Hq, cfg.d_v, dtype=cfg.dtype, device=dev)
+            l2 = torch.empty(cfg.B, cfg.Hq, cfg.S, dtype=torch.float32, device=dev)
+            fn = lambda: loza.loza_ssa_prefill(q2, k2, v2, o2, l2, cfg.n_sink, cfg.window, cfg.scale)
+            fn(); torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record(); torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            del q2, k2, v2, o2, l2
+            torch.cuda.empty_cache()
+            return ms
+        others = {}
+        ms2 = time_prefill(W.CFG2, 5)
+        if ms2 is not None:
+            others[W.CFG2.name] = {"prefill_ms": round(ms2, 3), "tflops": round(W.CFG2.flops() / (ms2 * 1e-3) / 1e12, 1),
+                                   "mfma_frac": round(W.CFG2.flops() / (ms2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        ms5 = time_prefill(W.CFG5, 2)
+        if ms5 is not None:
+            e5 = {"prefill_ms": round(ms5, 2), "tflops": round(W.CFG5.flops() / (ms5 * 1e-3) / 1e12, 1),
+                  "mfma_frac": round(W.CFG5.flops() / (ms5 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                  "us_per_token": round(ms5 * 1e3 / W.CFG5.S, 3)}
+            if "full_attention" in result:
+                # the comparator of this configuration: window = infinity on the first 131072 tokens
+                full_us_per_token = result["full_attention"]["prefill_ms"] * 1e3 / pc.S
+                e5["full_attention_128k_us_per_token"] = round(full_us_per_token, 3)
+                e5["per_token_speedup_vs_full_128k"] = round(full_us_per_token / (ms5 * 1e3 / W.CFG5.S), 2)
+            others[W.CFG5.name] = e5
+        result["other_configs"] = others
 
     print(json.dumps(result))
     return 0
