@@ -32,65 +32,10 @@
 #include <type_traits>
 
 #include "score_asm.h"
+#include "ssa_device.h"
 #include "ssa_kernels.h"
 
 namespace loza {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void *lds_void_ptr;
-typedef __attribute__((address_space(1))) const void *glb_void_ptr;
-
-#define LOZA_NEG_INF (-__builtin_inff())
-
-static __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
-{
-    bf16x2 v;
-    v[0] = (__bf16)a;  // round to nearest even
-    v[1] = (__bf16)b;
-    return __builtin_bit_cast(uint32_t, v);
-}
-
-// Workgroup barrier that orders LDS traffic only: in-flight global -> LDS tile copies of the
-// NEXT tile stay in flight across it (a barrier with a full memory fence would drain them).
-static __device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// max(x, value of x in the lane of the other wavefront half (lane ^ 32)), without touching LDS.
-static __device__ __forceinline__ float max_with_other_half(float x)
-{
-    const uint32_t u = __builtin_bit_cast(uint32_t, x);
-    // v_permlane32_swap exchanges one half of its first operand with the opposite half of the
-    // second; fed with two copies of x, one result holds the low half's values in both halves and
-    // the other the high half's, so their maximum is the wanted value in every lane
-    // (the copy and both results go through empty asm statements: the optimiser otherwise folds
-    // the maximum of the two results of a swap into the first result alone)
-    uint32_t u2 = u;
-    asm volatile("" : "+v"(u2));
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u2, false, false);
-    uint32_t r0 = r[0], r1 = r[1];
-    asm volatile("" : "+v"(r0), "+v"(r1));
-    return fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
-}
-
-static __device__ __forceinline__ float xor32(float x)
-{
-    // value held by the lane in the other half of the wavefront (lane ^ 32)
-    return __shfl_xor(x, 32, 64);
-}
-
-// s_waitcnt immediate for "at most n vector-memory operations outstanding" (gfx9 encoding:
-// vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt fields left at "no wait")
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 // RB: 32-row blocks per workgroup tile. Four wavefronts, one per SIMD.
 //   Prefill (RB = 4): every wave scores one row block and accumulates d_v / 4 output columns of
@@ -143,24 +88,6 @@ struct TileCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
-// First key of the window of query i: the window holds the `window` most recent blocks of `block`
-// tokens, the query's own block included (block = 1: the `window` most recent tokens).
-__device__ __forceinline__ int window_begin_of(int i, int window, int block)
-{
-    const int qb = block == 1 ? i : i / block;
-    return window > qb ? 0 : (qb - window + 1) * block;
-}
-
-// Positions below this take the two-term-P variant of the prefill kernel: with so few live keys
-// the output is as large as single value rows, and the bf16 rounding of P would be a visible share
-// of the error budget there. Beyond it every output averages enough keys for that to vanish.
-constexpr int kPrecisePositions = 128;
-
-// A decode query with fewer live keys than this is not worth a matrix-core pass and, with so few
-// terms, would show the bf16 rounding of the softmax weights in its output: the split kernel leaves
-// it alone and the merge kernel computes it directly in fp32.
-constexpr int kDirectKeys = 128;
-
 template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false, bool OUTF32 = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
@@ -178,6 +105,15 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 
     // ---- which tile of which (batch, kv head) ------------------------------------------------
     int id = blockIdx.x;
+    if (!DECODE && DQK == 128) {
+        // Workgroups go to the eight XCDs round-robin and every XCD has an L2 of its own. With one
+        // head per kv group a row tile is 128 positions, and 32 concurrent workgroups that are every
+        // eighth row tile make each L2 hold the keys of 32768 positions; handing every XCD one
+        // contiguous eighth of the tiles makes them consecutive row tiles (4096 positions).
+        // (Measured: a few per cent at 32K tokens. The wide shape, two positions per tile, loses.)
+        const int total = gridDim.x, chunk = total / 8;
+        if (id < chunk * 8) id = (id % 8) * chunk + id / 8;
+    }
     int split = 0;
     if (DECODE) { split = id % p.n_splits; id /= p.n_splits; }
     const int rt = p.rt_begin + p.row_tiles - 1 - (id % p.row_tiles);  // heaviest (latest) row tiles first
@@ -935,12 +871,19 @@ static bool pattern_needs_precise(const FwdParams &p)
     return live_at(kPrecisePositions - 1) < kPrecisePositions || (i0 < p.S && live_at(i0) < kPrecisePositions);
 }
 
-template <int DQK, int DV, bool ALIAS>
-static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
+// leading row tiles (128 rows each) of a plain prefill that take the two-term variant
+static int precise_row_tiles(const FwdParams &p)
 {
     const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
     int n_prec = (int)((prec_rows + 127) / 128);
     if (n_prec > p.row_tiles || pattern_needs_precise(p)) n_prec = p.row_tiles;
+    return n_prec;
+}
+
+template <int DQK, int DV, bool ALIAS>
+static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
+{
+    const int n_prec = precise_row_tiles(p);
     // the long tiles first: the short precise ones fill the tail
     if (p.out_f32 != nullptr) {
         hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, true>(p, n_prec, p.row_tiles - n_prec, stream);

@@ -64,7 +64,7 @@ CASES = [
     (4, 16, 1024, [999, 64, 65, 513], 0, 70, 256, None),     # pages larger than most windows
     (3, 64, 2048, [2048, 1025, 130], 1, 7, 128, 128),        # the paper's block pattern, page = block
     (3, 5, 512, [0, 200, 17], 4, 9, 64, None),               # an empty cache; short ones (direct path)
-    (1, 64, 700, [700], 7, None, 128, None),                 # window = infinity: every page is read
+    (1, 64, 768, [700], 7, None, 128, None),                 # window = infinity: every page is read
 ]
 
 
@@ -79,6 +79,8 @@ def test_mla_bf16_decode_paged(gpu_device, B, Hq, S_max, lens, ns, win, page, bl
     pages, table = _paginate(kc, lens, page, seed=5)
     out_p, lse_p = _run_paged(q, pages, pages, table, seqlens, ns, win, scale, 512, block)
     out_c, lse_c = H.run_decode(q, kc, kc, seqlens, ns, win, scale, d_v=512, block=block)
+    # (the same bits as long as both calls cut the keys into the same number of splits, which the
+    # cases arrange: where the pattern reaches the whole cache, its capacity is a multiple of the page)
     assert torch.equal(out_p.view(torch.int16), out_c.view(torch.int16)), "paged and contiguous decode differ"
     assert torch.equal(lse_p.view(torch.int32), lse_c.view(torch.int32))
     live = [b for b, L in enumerate(lens) if L > 0]
