@@ -169,6 +169,22 @@ int loza_ssa_extend_blocks(const void *q, const void *kcache, const void *vcache
                            int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
 
 /*
+ * loza_ssa_extend / loza_ssa_extend_blocks against a paged cache: k_pages, v_pages, block_table,
+ * num_pages, page_size, max_pages_per_seq as for loza_ssa_decode_paged below (same conditions on
+ * page_size and on the table entries), q, seqlens, out, lse as for loza_ssa_extend, with
+ * max_pages_per_seq * page_size in the place of S_max.
+ */
+int loza_ssa_extend_paged(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                          const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                          int64_t num_pages, int page_size, int max_pages_per_seq, int q_len, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale, void *stream);
+
+int loza_ssa_extend_paged_blocks(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                                 const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                                 int64_t num_pages, int page_size, int max_pages_per_seq, int q_len, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
+/*
  * SSA decode against a PAGED KV cache (the cache layout of a serving engine; the paper's
  * Efficiency section measures its decode kernel inside one). The rows of sequence b live in pages
  * of `page_size` rows: logical row j is row j % page_size of physical page

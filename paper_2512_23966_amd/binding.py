@@ -28,7 +28,7 @@ EXPORTS = (
     "loza_ssa_live_ranges_blocks", "loza_ssa_live_pairs_blocks",
     "loza_ssa_decode_paged", "loza_ssa_decode_paged_blocks",
     "loza_ssa_prefill_calibration_blocks", "loza_ssa_calibration_workspace_bytes",
-    "loza_ssa_extend", "loza_ssa_extend_blocks",
+    "loza_ssa_extend", "loza_ssa_extend_blocks", "loza_ssa_extend_paged", "loza_ssa_extend_paged_blocks",
 )
 
 
@@ -84,6 +84,10 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_extend.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_extend_blocks.restype = ci
         L.loza_ssa_extend_blocks.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, i64, i64, i64, f32, vp]
+        L.loza_ssa_extend_paged.restype = ci
+        L.loza_ssa_extend_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_extend_paged_blocks.restype = ci
+        L.loza_ssa_extend_paged_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, ci, i64, i64, i64, f32, vp]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -325,3 +329,39 @@ def loza_ssa_extend_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, lo
     """q_len new tokens per sequence against its cache, block-granular pattern."""
     _extend_common("loza_ssa_extend_blocks", q, kcache, vcache, seqlens, out, lse,
                    (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
+
+
+def _extend_paged_common(fn_name, q, k_pages, v_pages, block_table, seqlens, out, lse, pattern, scale, stream):
+    """bf16 SSA extend against a paged cache: q [B,q_len,Hq,d_qk], k_pages [num_pages,page_size,Hkv,d_qk],
+    v_pages likewise with d_v (or ``v_pages is k_pages``), block_table [B,max_pages] int32, seqlens [B] int32,
+    out [B,q_len,Hq,d_v] bf16, lse [B,Hq,q_len] fp32."""
+    B, q_len, Hq, d_qk = q.shape
+    num_pages, page_size, Hkv, _ = k_pages.shape
+    d_v = out.shape[3]
+    if k_pages.shape != (num_pages, page_size, Hkv, d_qk) or out.shape != (B, q_len, Hq, d_v) or lse.shape != (B, Hq, q_len) \
+            or seqlens.shape != (B,) or block_table.dim() != 2 or block_table.shape[0] != B:
+        raise ValueError("shape mismatch between q, k_pages, block_table, seqlens, out, lse")
+    if v_pages is not k_pages and v_pages.shape != (num_pages, page_size, Hkv, d_v):
+        raise ValueError("v_pages must be [num_pages, page_size, Hkv, d_v] (or the very tensor passed as k_pages)")
+    bf = torch.bfloat16
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(k_pages, bf, "k_pages")
+    vp = kp if v_pages is k_pages else _dev_ptr(v_pages, bf, "v_pages")
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(block_table, torch.int32, "block_table"),
+                                 _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                                 _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, num_pages, page_size,
+                                 block_table.shape[1], q_len, d_qk, d_v, *pattern, float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_extend_paged(q, k_pages, v_pages, block_table, seqlens, out, lse, n_sink, window, scale, stream=None):
+    """Extend against a paged cache, token-granular pattern (see :func:`_extend_paged_common`)."""
+    _extend_paged_common("loza_ssa_extend_paged", q, k_pages, v_pages, block_table, seqlens, out, lse,
+                         (int(n_sink), _win(window)), scale, stream)
+
+
+def loza_ssa_extend_paged_blocks(q, k_pages, v_pages, block_table, seqlens, out, lse, sink_blocks, local_blocks, block,
+                                 scale, stream=None):
+    """Extend against a paged cache, block-granular pattern."""
+    _extend_paged_common("loza_ssa_extend_paged_blocks", q, k_pages, v_pages, block_table, seqlens, out, lse,
+                         (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)

@@ -157,15 +157,44 @@ int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
     return T * (T + 1) / 2 + (S - T) * T;
 }
 
+// Paged cache description (block_table == nullptr: contiguous cache of S_max rows per sequence).
+struct Paging {
+    const int32_t *block_table;
+    int64_t num_pages;
+    int page_size, max_pages;
+};
+
+// Checks a paging description and gives log2(page_size) and the capacity per sequence in rows.
+static int check_paging(const Paging &pg, int *page_shift, int64_t *capacity)
+{
+    if (!pg.block_table) return LOZA_ERR_NULL;
+    // pages hold a power-of-two number of rows that key tiles (32 rows) divide
+    if (pg.page_size < 32 || (pg.page_size & (pg.page_size - 1)) != 0) return LOZA_ERR_SHAPE;
+    if (pg.num_pages < 1 || pg.num_pages > 2147483647LL || pg.max_pages < 1) return LOZA_ERR_SHAPE;
+    if ((int64_t)pg.max_pages * pg.page_size > kMaxSeq) return LOZA_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(pg.block_table) & 3u) return LOZA_ERR_ALIGN;
+    int s = 0;
+    while ((1 << s) < pg.page_size) ++s;
+    *page_shift = s;
+    *capacity = (int64_t)pg.max_pages * pg.page_size;
+    return LOZA_OK;
+}
+
 static int prefill_bf16(const void *q, const void *k, const void *v, void *out, float *lse,
                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                         int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream,
                         float *out_f32 = nullptr, bool validate_only = false,
-                        const int32_t *seqlens = nullptr, int64_t q_len = 0)
+                        const int32_t *seqlens = nullptr, int64_t q_len = 0, const Paging *paging = nullptr)
 {
     // seqlens != nullptr: "extend" form, q_len queries per sequence against a cache of S rows
+    // (with a paging description: of max_pages * page_size rows behind a block table)
     const bool extend = seqlens != nullptr;
     if (!q || !k || !v || (!out && !out_f32) || !lse) return LOZA_ERR_NULL;
+    int page_shift = 0;
+    if (paging) {
+        if (!extend) return LOZA_ERR_SHAPE;
+        if (int rc = check_paging(*paging, &page_shift, &S)) return rc;
+    }
     if (extend && (q_len < 1 || q_len > S || (reinterpret_cast<uintptr_t>(seqlens) & 3u))) return q_len < 1 || q_len > S ? LOZA_ERR_SHAPE : LOZA_ERR_ALIGN;
     if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
     if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
@@ -191,6 +220,10 @@ static int prefill_bf16(const void *q, const void *k, const void *v, void *out, 
     set_rescale_policy(p);
     if (extend) {
         p.seqlens = seqlens; p.q_len = (int)q_len;
+        if (paging) {
+            p.block_table = paging->block_table;
+            p.page_shift = page_shift; p.max_pages = paging->max_pages; p.num_pages = (int)paging->num_pages;
+        }
         return loza::launch_extend_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
     }
     return loza::launch_prefill_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
@@ -203,6 +236,28 @@ int loza_ssa_extend(const void *q, const void *kcache, const void *vcache, const
     if (!seqlens) return LOZA_ERR_NULL;
     return prefill_bf16(q, kcache, vcache, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false, scale, stream,
                         nullptr, false, seqlens, q_len);
+}
+
+int loza_ssa_extend_paged(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                          const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                          int64_t num_pages, int page_size, int max_pages_per_seq, int q_len, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    if (!seqlens) return LOZA_ERR_NULL;
+    const Paging pg{block_table, num_pages, page_size, max_pages_per_seq};
+    return prefill_bf16(q, k_pages, v_pages, out, lse, B, Hq, Hkv, 1, d_qk, d_v, n_sink, window, 1, false, scale, stream,
+                        nullptr, false, seqlens, q_len, &pg);
+}
+
+int loza_ssa_extend_paged_blocks(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                                 const int32_t *seqlens, void *out, float *lse, int B, int Hq, int Hkv,
+                                 int64_t num_pages, int page_size, int max_pages_per_seq, int q_len, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    if (!seqlens) return LOZA_ERR_NULL;
+    const Paging pg{block_table, num_pages, page_size, max_pages_per_seq};
+    return prefill_bf16(q, k_pages, v_pages, out, lse, B, Hq, Hkv, 1, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                        scale, stream, nullptr, false, seqlens, q_len, &pg);
 }
 
 int loza_ssa_extend_blocks(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens, void *out,
@@ -317,13 +372,6 @@ size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, in
     return (size_t)B * Hq * n * ((size_t)d_v + 4) * sizeof(float);
 }
 
-// Paged cache description (block_table == nullptr: contiguous cache of S_max rows per sequence).
-struct Paging {
-    const int32_t *block_table;
-    int64_t num_pages;
-    int page_size, max_pages;
-};
-
 static int decode_bf16(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                        void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
                        int d_qk, int d_v, int64_t sink, int64_t local, int64_t block, bool blocks, float scale,
@@ -332,14 +380,7 @@ static int decode_bf16(const void *q, const void *kcache, const void *vcache, co
     if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
     int page_shift = 0;
     if (paging) {
-        if (!paging->block_table) return LOZA_ERR_NULL;
-        // pages hold a power-of-two number of rows that key tiles (32 rows) divide
-        if (paging->page_size < 32 || (paging->page_size & (paging->page_size - 1)) != 0) return LOZA_ERR_SHAPE;
-        if (paging->num_pages < 1 || paging->num_pages > 2147483647LL || paging->max_pages < 1) return LOZA_ERR_SHAPE;
-        if ((int64_t)paging->max_pages * paging->page_size > kMaxSeq) return LOZA_ERR_SHAPE;
-        while ((1 << page_shift) < paging->page_size) ++page_shift;
-        S_max = (int64_t)paging->max_pages * paging->page_size;
-        if (reinterpret_cast<uintptr_t>(paging->block_table) & 3u) return LOZA_ERR_ALIGN;
+        if (int rc = check_paging(*paging, &page_shift, &S_max)) return rc;
     }
     if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, sink, local, scale)) return rc;
     if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }

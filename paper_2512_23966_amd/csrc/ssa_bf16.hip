@@ -88,7 +88,7 @@ struct TileCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
-template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false, bool OUTF32 = false>
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false, bool OUTF32 = false, bool EXT = false>
 __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 {
     using C = TileCfg<DQK, DV, RB, ALIAS, DECODE, PRECISE>;
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 
     // "Extend" prefill: the last q_len positions of each sequence are the queries, the keys come
     // from a cache whose valid length is seqlens[b] (q_len = 0: plain prefill, queries = keys = S).
-    const bool extend = !DECODE && p.q_len > 0;
+    constexpr bool extend = EXT;  // (its own instantiation: the plain prefill pays nothing for it)
     // valid key rows (a length beyond the cache is cut to the cache)
     const int64_t L = (DECODE || extend) ? ((int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S) : p.S;
     const int64_t Sq = extend ? (int64_t)p.q_len : p.S;           // query positions per sequence
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // A paged cache (decode only) keeps the rows of a sequence in pages of 2^page_shift rows that a
     // block table maps to physical pages; a key tile never straddles a page (pages hold a multiple
     // of N rows), so paging only changes where a tile starts.
-    const bool paged = DECODE && p.block_table != nullptr;
+    const bool paged = (DECODE || EXT) && p.block_table != nullptr;  // a plain prefill has no table
     const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
     const char *kbase = (const char *)p.k + (seq_row0 * p.Hkv + g) * (int64_t)DQK * 2;
     const char *vbase = (const char *)p.v + (seq_row0 * p.Hkv + g) * (int64_t)DV * 2;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // result usable. Between the two nothing may read the value; page_wait() returns it.
     auto page_request = [&](int t) -> int32_t {
         int32_t pid = 0;
-        if (DECODE && paged) {
+        if (paged) {
             const int64_t j0 = (int64_t)key_tile(t) * N;
             const int32_t *e = p.block_table + ((int64_t)b * p.max_pages + (j0 >> p.page_shift));
             asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pid) : "s"(e) : "memory");
@@ -225,13 +225,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         return pid;
     };
     auto page_wait = [&](int32_t pid) -> int32_t {
-        if (DECODE && paged) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pid) :: "memory");
+        if (paged) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pid) :: "memory");
         return pid;
     };
     // cache row (relative to kbase / vbase) at which key tile t starts, given its block-table entry
     auto tile_row = [&](int t, int32_t pid) -> int64_t {
         const int64_t j0 = (int64_t)key_tile(t) * N;
-        if (DECODE && paged) {
+        if (paged) {
             pid = pid < 0 ? 0 : (pid < p.num_pages ? pid : p.num_pages - 1);  // a bad entry stays in bounds
             return ((int64_t)pid << p.page_shift) + (j0 & ((1 << p.page_shift) - 1));
         }
@@ -837,12 +837,12 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParam
 
 // ---------------------------------------------------------------------------------------------------
 
-template <int DQK, int DV, bool ALIAS, bool PRECISE, bool OUTF32>
+template <int DQK, int DV, bool ALIAS, bool PRECISE, bool OUTF32, bool EXT = false>
 static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
 {
     if (rt_count <= 0) return hipSuccess;
     using C = TileCfg<DQK, DV, 4, ALIAS, false, PRECISE>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE, OUTF32>;
+    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE, OUTF32, EXT>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     p.rt_begin = rt_begin;
@@ -903,10 +903,10 @@ static hipError_t launch_extend_t(FwdParams p, hipStream_t stream)
 {
     p.all_precise = pattern_needs_precise(p) ? 1 : 0;
     if (!p.all_precise) {
-        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false>(p, 0, p.row_tiles, stream);
+        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false, true>(p, 0, p.row_tiles, stream);
         if (e != hipSuccess) return e;
     }
-    return launch_prefill_part<DQK, DV, ALIAS, true, false>(p, 0, p.row_tiles, stream);
+    return launch_prefill_part<DQK, DV, ALIAS, true, false, true>(p, 0, p.row_tiles, stream);
 }
 
 template <int DQK, int DV, bool ALIAS>

@@ -108,3 +108,39 @@ def test_single_token_chunk_agrees_with_decode(gpu_device):
     out_d, lse_d = H.run_decode(q[:, 0].contiguous(), kc, kc, seqlens, ns, win, scale, d_v=512)
     assert (out_e[:, 0].float() - out_d.float()).abs().max().item() <= 1.6e-2   # two independent bf16 roundings
     assert (lse_e[:, :, 0] - lse_d).abs().max().item() <= 1e-4
+
+
+# ---- extend against a paged cache ------------------------------------------------------------------
+
+def _run_paged(q, k_pages, v_pages, table, seqlens, pattern, scale, d_v, block=None):
+    B, q_len, Hq, _ = q.shape
+    out = torch.empty(B, q_len, Hq, d_v, dtype=torch.bfloat16, device=q.device)
+    lse = torch.empty(B, Hq, q_len, dtype=torch.float32, device=q.device)
+    if block is None:
+        loza.loza_ssa_extend_paged(q, k_pages, v_pages, table, seqlens, out, lse, pattern[0], pattern[1], scale)
+    else:
+        loza.loza_ssa_extend_paged_blocks(q, k_pages, v_pages, table, seqlens, out, lse, pattern[0], pattern[1], block, scale)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+@pytest.mark.parametrize("B,Hq,S_max,q_len,lens,ns,win,page,block", [
+    (3, 64, 640, 4, [600, 257, 131], 128, 100, 128, None),
+    (2, 64, 512, 37, [500, 300], 16, 64, 32, None),
+    (2, 64, 1536, 130, [1500, 1100], 1, 7, 128, 128),     # the paper's pattern, page = block
+    (2, 16, 512, 50, [400, 20], 8, 30, 64, None),          # a chunk longer than one of the caches
+])
+def test_mla_bf16_extend_paged_equals_contiguous(gpu_device, B, Hq, S_max, q_len, lens, ns, win, page, block):
+    from tests.test_gpu_parity_paged import _paginate
+    q = _rand((B, q_len, Hq, 576), 71, torch.bfloat16, gpu_device)
+    kc = _rand((B, S_max, 1, 576), 72, torch.bfloat16, gpu_device)
+    for b, L in enumerate(lens):
+        kc[b, L:] = float("nan")
+    seqlens = torch.tensor(lens, dtype=torch.int32, device=gpu_device)
+    scale = 192 ** -0.5
+    pages, table = _paginate(kc, lens, page, seed=3)
+    out_p, lse_p = _run_paged(q, pages, pages, table, seqlens, (ns, win), scale, 512, block)
+    out_c, lse_c = _run(q, kc, kc, seqlens, (ns, win), scale, 512, block)
+    assert torch.equal(out_p.view(torch.int16), out_c.view(torch.int16)), "paged and contiguous extend differ"
+    assert torch.equal(lse_p.view(torch.int32), lse_c.view(torch.int32))
+    _compare(q, kc, kc, lens, out_p, lse_p, (ns, win), scale, f"extend paged q{q_len} lens{lens} page{page} b{block}", block)

@@ -173,6 +173,19 @@ def test_extend_rejects_bad_arguments():
     assert B.lib().loza_ssa_extend_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, 64, 1, 4096, 4, 576, 512, 1, 7, 0, 0.07, None) == ERR_SHAPE
 
 
+def test_extend_paged_rejects_bad_paging():
+    def call(page_size=128, num_pages=100, max_pages=8, q_len=4, table=FAKE):
+        return B.lib().loza_ssa_extend_paged(FAKE, FAKE, FAKE, table, FAKE, FAKE, FAKE, 2, 64, 1, num_pages, page_size,
+                                             max_pages, q_len, 576, 512, 128, 256, 0.07, None)
+    assert call(page_size=96) == ERR_SHAPE
+    assert call(page_size=16) == ERR_SHAPE
+    assert call(num_pages=0) == ERR_SHAPE
+    assert call(max_pages=0) == ERR_SHAPE
+    assert call(q_len=2000) == ERR_SHAPE       # more queries than the table can hold rows
+    assert call(table=None) == ERR_NULL
+    assert call(table=FAKE + 2) == ERR_ALIGN
+
+
 # ---- argument validation: every case returns before the first HIP call --------------------------
 
 FAKE = 0x1000  # aligned, non-null, never dereferenced: validation fails first
