@@ -1,8 +1,15 @@
-// bf16 streaming-sparse-attention kernels for gfx950 (MI355X): prefill and split-key decode.
+// bf16 streaming-sparse-attention kernels for gfx950 (MI355X): prefill, extend and split-key decode.
 //
 // What is computed: O* = softmax(scale * Q K*^T) V* over the live key set of every query
-// (paper: Architecture section, Eq. 2 / Eq. 4; with window >= S this is Eq. 1), plus the natural
-// log of the softmax denominator.  live(i) = { j <= i : j < n_sink or i - j < window }.
+// (paper: Architecture section, Eq. 2 / Eq. 4; with a window that covers everything this is Eq. 1),
+// plus the natural log of the softmax denominator. The live set of query i is
+//   { j <= i : j < n_sink  or  j >= max(0, i / block - window + 1) * block },
+// which is the paper's block-granular pattern (sink blocks, local blocks, block size) and, with
+// block = 1, the token-granular one (the `window` most recent keys, the query's own included).
+// Three forms share one kernel template: prefill (queries = keys = S positions), extend (the q_len
+// newest positions of every sequence against its cache, lengths on the device) and decode (one
+// query per sequence, the live keys split over several workgroups and merged by a second kernel);
+// extend and decode can read a paged cache through a block table.
 //
 // How it is mapped to the machine (one workgroup = 4 wavefronts = 1 per SIMD; prefill tiles hold
 // 128 query rows and all four waves score, decode tiles hold 64 rows (the heads of one token) and

@@ -194,3 +194,40 @@ def test_decode_equals_last_prefill_row_and_split_count_does_not_matter(gpu_devi
     for o, l in results[1:]:
         assert (o - results[0][0]).abs().max().item() <= 1.6e-2
         assert (l - results[0][1]).abs().max().item() <= 1e-4
+
+
+def test_mla_shape_with_two_latent_heads(gpu_device):
+    """The wide shape with Hkv = 2 (rows of the cache are strided by two heads): prefill and decode."""
+    B, S, Hq, Hkv, ns, win = 1, 300, 8, 2, 16, 70
+    q = _rand((B, S, Hq, 576), 201, torch.bfloat16, gpu_device)
+    k = _rand((B, S, Hkv, 576), 202, torch.bfloat16, gpu_device)
+    scale = 192 ** -0.5
+    out, lse = H.run_prefill(q, k, k, ns, win, scale, d_v=512)
+    rb, rh, ri = H.all_rows(B, Hq, S)
+    H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, "mla Hkv2 prefill")
+    lens = [300, 180]
+    qd = _rand((2, Hq, 576), 203, torch.bfloat16, gpu_device)
+    kc = _rand((2, S, Hkv, 576), 204, torch.bfloat16, gpu_device)
+    seqlens = torch.tensor(lens, dtype=torch.int32, device=gpu_device)
+    out_d, lse_d = H.run_decode(qd, kc, kc, seqlens, ns, win, scale, d_v=512)
+    rb = np.repeat(np.arange(2, dtype=np.int64), Hq)
+    rh = np.tile(np.arange(Hq, dtype=np.int64), 2)
+    H.compare_decode(qd, kc, kc, seqlens, out_d, lse_d, rb, rh, ns, win, scale, "mla Hkv2 decode")
+
+
+def test_calls_run_on_the_stream_they_are_given(gpu_device):
+    """Work queued on a side stream behind a long-running kernel must not be visible before that
+    stream is waited for, and must be complete after: the launches go where the caller says."""
+    q = _rand((1, 600, 64, 576), 211, torch.bfloat16, gpu_device)
+    k = _rand((1, 600, 1, 576), 212, torch.bfloat16, gpu_device)
+    ref_out, ref_lse = H.run_prefill(q, k, k, 16, 130, 0.07, d_v=512)
+    side = torch.cuda.Stream(device=gpu_device)
+    out = torch.zeros_like(ref_out)
+    lse = torch.zeros_like(ref_lse)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        loza.loza_ssa_prefill(q, k, k, out, lse, 16, 130, 0.07)           # picks up the current (side) stream
+    loza.loza_ssa_prefill(q, k, k, out, lse, 16, 130, 0.07, stream=side)  # and an explicit one
+    side.synchronize()
+    assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
+    assert torch.equal(lse.view(torch.int32), ref_lse.view(torch.int32))
