@@ -231,3 +231,16 @@ def test_calls_run_on_the_stream_they_are_given(gpu_device):
     side.synchronize()
     assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
     assert torch.equal(lse.view(torch.int32), ref_lse.view(torch.int32))
+
+
+def test_decode_length_beyond_the_cache_is_cut_to_it(gpu_device):
+    B, Hq, S_max, ns, win = 2, 64, 500, 16, 200
+    q = _rand((B, Hq, 576), 221, torch.bfloat16, gpu_device)
+    kc = _rand((B, S_max, 1, 576), 222, torch.bfloat16, gpu_device)
+    scale = 192 ** -0.5
+    exact = torch.tensor([S_max, S_max], dtype=torch.int32, device=gpu_device)
+    beyond = torch.tensor([S_max + 100, 2 ** 31 - 1], dtype=torch.int32, device=gpu_device)
+    a = H.run_decode(q, kc, kc, exact, ns, win, scale, d_v=512)
+    c = H.run_decode(q, kc, kc, beyond, ns, win, scale, d_v=512)
+    assert torch.equal(a[0].view(torch.int16), c[0].view(torch.int16))
+    assert torch.equal(a[1].view(torch.int32), c[1].view(torch.int32))
