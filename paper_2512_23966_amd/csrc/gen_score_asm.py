@@ -34,12 +34,13 @@ def body(ks: int, depth: int) -> str:
     return "".join(f'    "{l}\\n"\n' for l in lines)
 
 
-def body_copy(ks: int, depth: int, n_copy: int, waves: int) -> str:
+def body_copy(ks: int, depth: int, n_copy: int, waves: int, hint: str = "") -> str:
     """Score phase with the global -> LDS copy of a later key tile woven in: one
     global_load_lds_dwordx4 every few matrix instructions, so that issuing the copy costs the
     matrix cores nothing. Extra operands after the query fragments: n_copy per-lane byte offsets,
     the largest valid offset (SGPR), the tile's global base (SGPR pair), the LDS base of this
-    wave's first chunk (SGPR), and a scratch VGPR (output)."""
+    wave's first chunk (SGPR), and a scratch VGPR (output). `hint`: cache-policy modifier of the
+    copy instructions (" nt" for data that is read once)."""
     t = lambda i: f"%{1 + i}"
     tmp = f"%{depth + 1}"                      # scratch VGPR (early-clobber output)
     addr = f"%{depth + 2}"
@@ -63,24 +64,27 @@ def body_copy(ks: int, depth: int, n_copy: int, waves: int) -> str:
             lines.append(f"v_min_u32 {tmp}, {kmax}, {voff(c)}")
             lines.append(f"s_add_u32 m0, {m0b}, {c * waves * 1024}")
             lines.append("s_nop 0")
-            lines.append(f"global_load_lds_dwordx4 {tmp}, {src}")
+            lines.append(f"global_load_lds_dwordx4 {tmp}, {src}{hint}")
             c += 1
     assert c == n_copy
     lines += ["s_nop 7", "s_nop 7", "s_nop 7"]
     return "".join(f'    "{l}\\n"\n' for l in lines)
 
 
-def macro_copy(dqk: int, n_copy: int, waves: int) -> str:
+def macro_copy(dqk: int, n_copy: int, waves: int, hint: str = "") -> str:
     ks = dqk // 16
     depth = min(DEPTH, ks)
     outs = ['"=&v"(s_)'] + [f'"=&v"(kf_[{d}])' for d in range(depth)] + ['"=&v"(tmp_)']
     ins = ['"v"(addr_)'] + [f'"v"(qf_[{kk}])' for kk in range(ks)] + [f'"v"(voff_[{c}])' for c in range(n_copy)]
     ins += ['"s"(kmax_)', '"s"(src_)', '"s"(m0base_)']
-    text = f"// d_qk = {dqk}, {waves} waves per workgroup: as above, plus {n_copy} copy instructions of a later key tile\n"
-    text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY_W{waves}(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
-    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, waves).splitlines(True))
+    suffix = "_" + hint.strip().upper() if hint else ""
+    text = f"// d_qk = {dqk}, {waves} waves per workgroup: as above, plus {n_copy} copy instructions of a later key tile"
+    text += f" (cache policy:{hint})\n" if hint else "\n"
+    text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY_W{waves}{suffix}(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
+    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, waves, hint).splitlines(True))
     text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\")\n"
-    text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
+    if not hint:
+        text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
     return text
 
 
@@ -103,4 +107,5 @@ if __name__ == "__main__":
     for dqk in (576, 128):
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
+    print(macro_copy(576, 9, 4, " nt"))
     print("#endif")
