@@ -50,6 +50,9 @@ def _load():
         lib.oracle_ssa_live_mask_blocks.argtypes = [i64, i64, i64, i64, i64, vp]
         lib.oracle_ssa_count_pairs_blocks.restype = i64
         lib.oracle_ssa_count_pairs_blocks.argtypes = [i64, i64, i64, i64]
+        lib.oracle_ssa_backward.restype = ci
+        lib.oracle_ssa_backward.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, i64, ci, ci, i64, i64,
+                                            i64, i64, i64, ctypes.c_double, vp, vp, vp, ci]
         _lib = lib
     return _lib
 
@@ -169,3 +172,37 @@ def calibration_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, sink_blocks, loca
                                     block=block, scale=scale, n_threads=n_threads)
     a = float(alpha)
     return a * o_full + (1.0 - a) * o_sparse, o_full, o_sparse, lse_full, lse_sparse
+
+
+def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=None):
+    """Gradient of SSA (Eq. 4) with respect to Q, K and V for the scalar ``sum(dout * O)``.
+
+    q [B, S, Hq, d_qk]; k [B, S, Hkv, d_qk]; v [B, S, Hkv, d_v] or ``("alias", d_v)``; dout
+    [B, S, Hq, d_v]. Pattern arguments as in :func:`ssa_rows`. Rows whose ``dout`` is zero
+    everywhere are skipped (they contribute exactly nothing). Returns float64 arrays
+    (dq [B, S, Hq, d_qk], dk [B, S, Hkv, d_qk], dv [B, S, Hkv, d_v]); with aliased values the
+    gradient with respect to the shared tensor is ``dk`` with ``dv`` added to its first d_v columns.
+    """
+    lib = _load()
+    qa, ka, da = as_oracle_array(q), as_oracle_array(k), as_oracle_array(dout)
+    if isinstance(v, tuple) and v[0] == "alias":
+        va, d_v, v_stride = ka, int(v[1]), ka.shape[3]
+    else:
+        va = as_oracle_array(v)
+        d_v, v_stride = va.shape[3], va.shape[3]
+    if not (qa.dtype == ka.dtype == va.dtype == da.dtype):
+        raise TypeError("q, k, v, dout must share a dtype")
+    B, S, Hkv, k_stride = ka.shape
+    _, _, Hq, d_qk = qa.shape
+    assert qa.shape == (B, S, Hq, d_qk) and da.shape == (B, S, Hq, d_v)
+    dq = np.empty((B, S, Hq, d_qk), dtype=np.float64)
+    dk = np.empty((B, S, Hkv, d_qk), dtype=np.float64)
+    dv = np.empty((B, S, Hkv, d_v), dtype=np.float64)
+    rc = lib.oracle_ssa_backward(qa.ctypes.data, ka.ctypes.data, va.ctypes.data, da.ctypes.data, _dtype_code(qa),
+                                 B, Hq, Hkv, S, d_qk, d_v, k_stride, v_stride,
+                                 int(n_sink), min(int(window), INT64_MAX), 0 if block is None else int(block),
+                                 float(scale), dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
+                                 int(n_threads or host_threads()))
+    if rc != 0:
+        raise RuntimeError(f"oracle_ssa_backward failed with code {rc}")
+    return dq, dk, dv

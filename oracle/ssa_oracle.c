@@ -250,3 +250,207 @@ int64_t oracle_ssa_count_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t lo
         for (int64_t j = 0; j <= i; ++j) n += alive_blocks(i, j, sink_blocks, local_blocks, block);
     return n;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Gradient of SSA (what the sparse mid-training of the Architecture section's Training paragraph
+ * differentiates): for the scalar L = sum over rows of <dO_row, O_row>, with O from Eq. 4 under the
+ * same live sets, the derivatives with respect to Q, K and V by the chain rule of a softmax:
+ *
+ *   p_ij  = exp(scale q_i.k_j - lse_i)   for live j, 0 otherwise
+ *   dV_j  = sum_i p_ij dO_i
+ *   dP_ij = dO_i . v_j ,   D_i = dO_i . O_i (= sum_j p_ij dP_ij)
+ *   dS_ij = p_ij (dP_ij - D_i)
+ *   dQ_i  = scale sum_j dS_ij k_j ,   dK_j = scale sum_i dS_ij q_i
+ *
+ * (sums over i run over every query row -- all heads of the key's group -- that sees key j).
+ * Nothing is saved from a forward pass: every row's scores, maximum, denominator and output are
+ * recomputed here from the definition.  A row whose dO is zero everywhere contributes exactly
+ * nothing and is skipped, which lets a test at full sequence length put its dO on a few rows.
+ * dK and dV are always returned separately; when V is a prefix of K (absorbed MLA) the gradient
+ * with respect to the shared tensor is their sum, which the caller forms.
+ *
+ * Pins (tests/test_oracle_pins_backward.py): reverse-mode differentiation of a library attention
+ * routine under a mask built from Python sets, central finite differences of this file's own
+ * forward, the closed form for Q = 0, and the row-sum identities sum_j dS_ij = 0.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    const void *q, *k, *v, *dout;
+    int dtype;
+    int B, Hq, Hkv;
+    int64_t S;
+    int d_qk, d_v;
+    int64_t k_row_stride, v_row_stride;
+    int64_t n_sink, window, block;
+    double scale;
+    int64_t n_rows;
+    const int64_t *rows;   /* flat (b * S + i) * Hq + h of the rows with a nonzero dO */
+    double *row_lse, *row_D;
+    double *dq, *dk, *dv;
+    int64_t next;          /* shared work counter */
+    int failed;
+} bwd_t;
+
+static int bwd_alive(const bwd_t *J, int64_t i, int64_t j)
+{
+    return J->block > 0 ? alive_blocks(i, j, J->n_sink, J->window, J->block) : alive(i, j, J->n_sink, J->window);
+}
+
+/* pass 1, one row: forward from the definition, then dQ of the row; keeps lse and D of the row */
+static int bwd_row(bwd_t *J, int64_t r, double *score, double *o)
+{
+    const int64_t flat = J->rows[r];
+    const int64_t h = flat % J->Hq, bi = flat / J->Hq, i = bi % J->S, b = bi / J->S;
+    const int64_t g = h / (J->Hq / J->Hkv);
+    const int64_t S = J->S;
+    const int64_t qbase = flat * J->d_qk, dobase = flat * J->d_v;
+    double m = -INFINITY;
+    int64_t n_alive = 0;
+    for (int64_t j = 0; j < S; ++j) {
+        if (!bwd_alive(J, i, j)) { score[j] = -INFINITY; continue; }
+        const int64_t kbase = ((b * S + j) * J->Hkv + g) * J->k_row_stride;
+        double dot = 0.0;
+        for (int c = 0; c < J->d_qk; ++c) dot += widen(J->q, J->dtype, qbase + c) * widen(J->k, J->dtype, kbase + c);
+        score[j] = J->scale * dot;
+        if (score[j] > m) m = score[j];
+        ++n_alive;
+    }
+    if (n_alive == 0) return -1;
+    double l = 0.0;
+    for (int64_t j = 0; j < S; ++j)
+        if (score[j] != -INFINITY) l += exp(score[j] - m);
+    const double lse = m + log(l);
+    for (int c = 0; c < J->d_v; ++c) o[c] = 0.0;
+    for (int64_t j = 0; j < S; ++j) {
+        if (score[j] == -INFINITY) continue;
+        const double p = exp(score[j] - lse);
+        const int64_t vbase = ((b * S + j) * J->Hkv + g) * J->v_row_stride;
+        for (int c = 0; c < J->d_v; ++c) o[c] += p * widen(J->v, J->dtype, vbase + c);
+    }
+    double D = 0.0;
+    for (int c = 0; c < J->d_v; ++c) D += widen(J->dout, J->dtype, dobase + c) * o[c];
+    double *dq = J->dq + qbase;
+    for (int c = 0; c < J->d_qk; ++c) dq[c] = 0.0;
+    for (int64_t j = 0; j < S; ++j) {
+        if (score[j] == -INFINITY) continue;
+        const double p = exp(score[j] - lse);
+        const int64_t vbase = ((b * S + j) * J->Hkv + g) * J->v_row_stride;
+        const int64_t kbase = ((b * S + j) * J->Hkv + g) * J->k_row_stride;
+        double dP = 0.0;
+        for (int c = 0; c < J->d_v; ++c) dP += widen(J->dout, J->dtype, dobase + c) * widen(J->v, J->dtype, vbase + c);
+        const double dS = p * (dP - D);
+        for (int c = 0; c < J->d_qk; ++c) dq[c] += J->scale * dS * widen(J->k, J->dtype, kbase + c);
+    }
+    J->row_lse[r] = lse;
+    J->row_D[r] = D;
+    return 0;
+}
+
+static void *bwd_worker_rows(void *arg)
+{
+    bwd_t *J = (bwd_t *)arg;
+    double *score = (double *)malloc((size_t)J->S * sizeof(double));
+    double *o = (double *)malloc((size_t)J->d_v * sizeof(double));
+    if (!score || !o) { __atomic_store_n(&J->failed, 1, __ATOMIC_SEQ_CST); free(score); free(o); return NULL; }
+    for (;;) {
+        int64_t r = __atomic_fetch_add(&J->next, 1, __ATOMIC_SEQ_CST);
+        if (r >= J->n_rows) break;
+        if (bwd_row(J, r, score, o) != 0) __atomic_store_n(&J->failed, 2, __ATOMIC_SEQ_CST);
+    }
+    free(score); free(o);
+    return NULL;
+}
+
+/* pass 2, one key (b, j, g): dK and dV of that key, summed over the rows that see it in list order */
+static void bwd_key(bwd_t *J, int64_t key)
+{
+    const int64_t g = key % J->Hkv, bj = key / J->Hkv, j = bj % J->S, b = bj / J->S;
+    const int group = J->Hq / J->Hkv;
+    const int64_t kbase = key * J->k_row_stride, vbase = key * J->v_row_stride;
+    double *dk = J->dk + key * (int64_t)J->d_qk, *dv = J->dv + key * (int64_t)J->d_v;
+    for (int64_t r = 0; r < J->n_rows; ++r) {
+        const int64_t flat = J->rows[r];
+        const int64_t h = flat % J->Hq, bi = flat / J->Hq, i = bi % J->S, rb = bi / J->S;
+        if (rb != b || h / group != g || !bwd_alive(J, i, j)) continue;
+        const int64_t qbase = flat * J->d_qk, dobase = flat * J->d_v;
+        double dot = 0.0, dP = 0.0;
+        for (int c = 0; c < J->d_qk; ++c) dot += widen(J->q, J->dtype, qbase + c) * widen(J->k, J->dtype, kbase + c);
+        for (int c = 0; c < J->d_v; ++c) dP += widen(J->dout, J->dtype, dobase + c) * widen(J->v, J->dtype, vbase + c);
+        const double p = exp(J->scale * dot - J->row_lse[r]);
+        const double dS = p * (dP - J->row_D[r]);
+        for (int c = 0; c < J->d_qk; ++c) dk[c] += J->scale * dS * widen(J->q, J->dtype, qbase + c);
+        for (int c = 0; c < J->d_v; ++c) dv[c] += p * widen(J->dout, J->dtype, dobase + c);
+    }
+}
+
+static void *bwd_worker_keys(void *arg)
+{
+    bwd_t *J = (bwd_t *)arg;
+    const int64_t n_keys = (int64_t)J->B * J->S * J->Hkv;
+    for (;;) {
+        int64_t key = __atomic_fetch_add(&J->next, 1, __ATOMIC_SEQ_CST);
+        if (key >= n_keys) break;
+        bwd_key(J, key);
+    }
+    return NULL;
+}
+
+static void bwd_run(bwd_t *J, void *(*fn)(void *), int n_threads)
+{
+    pthread_t tid[256];
+    int started = 0;
+    J->next = 0;
+    for (int t = 1; t < n_threads; ++t)
+        if (pthread_create(&tid[started], NULL, fn, J) == 0) ++started;
+    fn(J);
+    for (int t = 0; t < started; ++t) pthread_join(tid[t], NULL);
+}
+
+/*
+ *   q    [B, S, Hq, d_qk]            dout [B, S, Hq, d_v]
+ *   k    [B, S, Hkv, k_row_stride]   v    [B, S, Hkv, v_row_stride]  (v may alias k, as in the forward)
+ *   dq   [B, S, Hq, d_qk] fp64       dk   [B, S, Hkv, d_qk] fp64       dv [B, S, Hkv, d_v] fp64
+ *   block = 0: token-granular pattern (n_sink, window in tokens); block > 0: sink blocks, local blocks.
+ * Returns 0, -1 on a bad argument, -2 if a contributing row has no live key, -3 on allocation failure.
+ */
+int oracle_ssa_backward(const void *q, const void *k, const void *v, const void *dout, int dtype,
+                        int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                        int64_t k_row_stride, int64_t v_row_stride,
+                        int64_t n_sink, int64_t window, int64_t block, double scale,
+                        double *dq, double *dk, double *dv, int n_threads)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv) return -1;
+    if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || d_qk < 1 || d_v < 1) return -1;
+    if (k_row_stride < d_qk || v_row_stride < d_v || n_sink < 0 || window < 1 || block < 0) return -1;
+
+    const int64_t n_all = (int64_t)B * S * Hq;
+    int64_t *rows = (int64_t *)malloc((size_t)n_all * sizeof(int64_t));
+    if (!rows) return -3;
+    int64_t n_rows = 0;
+    for (int64_t r = 0; r < n_all; ++r) {
+        int any = 0;
+        for (int c = 0; c < d_v && !any; ++c) any = widen(dout, dtype, r * d_v + c) != 0.0;
+        if (any) rows[n_rows++] = r;
+    }
+    memset(dq, 0, (size_t)n_all * d_qk * sizeof(double));
+    memset(dk, 0, (size_t)B * S * Hkv * d_qk * sizeof(double));
+    memset(dv, 0, (size_t)B * S * Hkv * d_v * sizeof(double));
+
+    bwd_t J;
+    memset(&J, 0, sizeof J);
+    J.q = q; J.k = k; J.v = v; J.dout = dout; J.dtype = dtype; J.B = B; J.Hq = Hq; J.Hkv = Hkv; J.S = S;
+    J.d_qk = d_qk; J.d_v = d_v; J.k_row_stride = k_row_stride; J.v_row_stride = v_row_stride;
+    J.n_sink = n_sink; J.window = window; J.block = block; J.scale = scale;
+    J.n_rows = n_rows; J.rows = rows; J.dq = dq; J.dk = dk; J.dv = dv;
+    J.row_lse = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
+    J.row_D = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
+    if (!J.row_lse || !J.row_D) { free(rows); free(J.row_lse); free(J.row_D); return -3; }
+    if (n_threads < 1) n_threads = 1;
+    if (n_threads > 256) n_threads = 256;
+    bwd_run(&J, bwd_worker_rows, n_threads);
+    if (!J.failed) bwd_run(&J, bwd_worker_keys, n_threads);
+    free(rows); free(J.row_lse); free(J.row_D);
+    if (J.failed == 1) return -3;
+    if (J.failed == 2) return -2;
+    return 0;
+}
