@@ -236,6 +236,50 @@ int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void
 /* Host-only. Workspace bytes of loza_ssa_prefill_calibration_blocks (0 on invalid sizes). */
 size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v);
 
+/*
+ * SSA backward: the gradients of loza_ssa_prefill's output with respect to q, k and v, over live
+ * (query, key) pairs only. This is what training a sparsified model differentiates (paper:
+ * Architecture section, Eq. 4 and its Training paragraph; the paper states no formulas, they are the
+ * chain rule of a softmax):
+ *     p_ij = exp(scale q_i.k_j - lse_i) for live j,  D_i = dout_i . out_i,
+ *     dv_j = sum_i p_ij dout_i,  ds_ij = p_ij (dout_i . v_j - D_i),
+ *     dq_i = scale sum_j ds_ij k_j,  dk_j = scale sum_i ds_ij q_i,
+ * the sums over i taking every query head of the key's group.
+ *   q, k, v     as loza_ssa_prefill (bf16; v == k allowed)
+ *   out  [B, S, Hq, d_v] bf16 and lse [B, Hq, S] fp32: what loza_ssa_prefill returned for q, k, v
+ *   dout [B, S, Hq, d_v] bf16: gradient arriving at out
+ *   dq   [B, S, Hq, d_qk] bf16      dk [B, S, Hkv, d_qk] bf16      dv [B, S, Hkv, d_v] bf16
+ *        When v == k, the one tensor serves as keys and (its first d_v columns) as values; dk then
+ *        receives the gradient with respect to that tensor (dk with dv added to its first d_v
+ *        columns) and dv is ignored (may be NULL).
+ *   workspace: loza_ssa_backward_workspace_bytes(...) bytes of device memory, 16-byte aligned;
+ *        contents on entry are ignored. Two calls that overlap in time need two workspaces.
+ * Supported: the (d_qk, d_v) pairs of loza_ssa_prefill, scale > 0, and Hq / Hkv a power of two up to
+ * 32 or a multiple of 32 (else LOZA_ERR_UNSUPPORTED). Arithmetic: bf16 matrix-core operands (q, k,
+ * v, dout, and p and ds rounded to bf16), fp32 accumulation, one rounding of each result to bf16.
+ * Sums run in a fixed order: the result is deterministic. No output aliases an input.
+ */
+int loza_ssa_backward(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                      const void *dout, void *dq, void *dk, void *dv,
+                      int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                      int64_t n_sink, int64_t window, float scale,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same under the block-granular pattern of loza_ssa_prefill_blocks. */
+int loza_ssa_backward_blocks(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                             const void *dout, void *dq, void *dk, void *dv,
+                             int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                             int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only. Workspace bytes of loza_ssa_backward / loza_ssa_backward_blocks for these sizes
+ * (v_aliases_k: nonzero when v == k will be passed); 0 on sizes the call would reject. */
+size_t loza_ssa_backward_workspace_bytes(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                         int64_t n_sink, int64_t window, int v_aliases_k);
+size_t loza_ssa_backward_workspace_bytes_blocks(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                                int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                                int v_aliases_k);
+
 /* Host-only twins of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern. */
 int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                 int64_t *sink_end, int64_t *win_begin, int64_t *win_end);

@@ -52,7 +52,7 @@ def _load():
         lib.oracle_ssa_count_pairs_blocks.argtypes = [i64, i64, i64, i64]
         lib.oracle_ssa_backward.restype = ci
         lib.oracle_ssa_backward.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, i64, ci, ci, i64, i64,
-                                            i64, i64, i64, ctypes.c_double, vp, vp, vp, ci]
+                                            i64, i64, i64, ctypes.c_double, vp, vp, vp, vp, vp, ci]
         _lib = lib
     return _lib
 
@@ -174,12 +174,15 @@ def calibration_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, sink_blocks, loca
     return a * o_full + (1.0 - a) * o_sparse, o_full, o_sparse, lse_full, lse_sparse
 
 
-def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=None):
+def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=None, out=None, lse=None):
     """Gradient of SSA (Eq. 4) with respect to Q, K and V for the scalar ``sum(dout * O)``.
 
     q [B, S, Hq, d_qk]; k [B, S, Hkv, d_qk]; v [B, S, Hkv, d_v] or ``("alias", d_v)``; dout
     [B, S, Hq, d_v]. Pattern arguments as in :func:`ssa_rows`. Rows whose ``dout`` is zero
-    everywhere are skipped (they contribute exactly nothing). Returns float64 arrays
+    everywhere are skipped (they contribute exactly nothing). ``out`` [B, S, Hq, d_v] (dtype of q)
+    and ``lse`` [B, Hq, S] float32, given together, are what a forward pass stored: D and the weights
+    are then taken from them as a training step does, instead of from a forward recomputed here.
+    Returns float64 arrays
     (dq [B, S, Hq, d_qk], dk [B, S, Hkv, d_qk], dv [B, S, Hkv, d_v]); with aliased values the
     gradient with respect to the shared tensor is ``dk`` with ``dv`` added to its first d_v columns.
     """
@@ -195,13 +198,23 @@ def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=
     B, S, Hkv, k_stride = ka.shape
     _, _, Hq, d_qk = qa.shape
     assert qa.shape == (B, S, Hq, d_qk) and da.shape == (B, S, Hq, d_v)
+    oa = la = None
+    if (out is None) != (lse is None):
+        raise ValueError("out and lse come together")
+    if out is not None:
+        oa = as_oracle_array(out)
+        la = as_oracle_array(lse)
+        if oa.dtype != qa.dtype or oa.shape != (B, S, Hq, d_v) or la.dtype != np.float32 or la.shape != (B, Hq, S):
+            raise TypeError("out must be [B, S, Hq, d_v] in the dtype of q, lse [B, Hq, S] float32")
     dq = np.empty((B, S, Hq, d_qk), dtype=np.float64)
     dk = np.empty((B, S, Hkv, d_qk), dtype=np.float64)
     dv = np.empty((B, S, Hkv, d_v), dtype=np.float64)
     rc = lib.oracle_ssa_backward(qa.ctypes.data, ka.ctypes.data, va.ctypes.data, da.ctypes.data, _dtype_code(qa),
                                  B, Hq, Hkv, S, d_qk, d_v, k_stride, v_stride,
                                  int(n_sink), min(int(window), INT64_MAX), 0 if block is None else int(block),
-                                 float(scale), dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
+                                 float(scale), oa.ctypes.data if oa is not None else None,
+                                 la.ctypes.data if la is not None else None,
+                                 dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
                                  int(n_threads or host_threads()))
     if rc != 0:
         raise RuntimeError(f"oracle_ssa_backward failed with code {rc}")

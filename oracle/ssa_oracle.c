@@ -263,9 +263,14 @@ int64_t oracle_ssa_count_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t lo
  *   dQ_i  = scale sum_j dS_ij k_j ,   dK_j = scale sum_i dS_ij q_i
  *
  * (sums over i run over every query row -- all heads of the key's group -- that sees key j).
- * Nothing is saved from a forward pass: every row's scores, maximum, denominator and output are
- * recomputed here from the definition.  A row whose dO is zero everywhere contributes exactly
- * nothing and is skipped, which lets a test at full sequence length put its dO on a few rows.
+ * By default nothing is saved from a forward pass: every row's scores, maximum, denominator and
+ * output are recomputed here from the definition.  A training step does not recompute them: it
+ * hands the backward the `out` and `lse` its forward produced, rounded to their storage types, and
+ * takes D_i and p_ij from those.  With `out_saved` / `lse_saved` given, this file does the same
+ * substitution (D_i = dO_i . out_saved_i, p_ij = exp(scale q_i.k_j - lse_saved_i)) and nothing else
+ * changes; given its own forward's values it returns the gradient itself.  A row whose dO is zero
+ * everywhere contributes exactly nothing and is skipped, which lets a test at full sequence length
+ * put its dO on a few rows.
  * dK and dV are always returned separately; when V is a prefix of K (absorbed MLA) the gradient
  * with respect to the shared tensor is their sum, which the caller forms.
  *
@@ -275,6 +280,8 @@ int64_t oracle_ssa_count_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t lo
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
     const void *q, *k, *v, *dout;
+    const void *out_saved;   /* NULL, or [B, S, Hq, d_v] in the inputs' dtype */
+    const float *lse_saved;  /* NULL, or [B, Hq, S] fp32 */
     int dtype;
     int B, Hq, Hkv;
     int64_t S;
@@ -318,13 +325,18 @@ static int bwd_row(bwd_t *J, int64_t r, double *score, double *o)
     double l = 0.0;
     for (int64_t j = 0; j < S; ++j)
         if (score[j] != -INFINITY) l += exp(score[j] - m);
-    const double lse = m + log(l);
-    for (int c = 0; c < J->d_v; ++c) o[c] = 0.0;
-    for (int64_t j = 0; j < S; ++j) {
-        if (score[j] == -INFINITY) continue;
-        const double p = exp(score[j] - lse);
-        const int64_t vbase = ((b * S + j) * J->Hkv + g) * J->v_row_stride;
-        for (int c = 0; c < J->d_v; ++c) o[c] += p * widen(J->v, J->dtype, vbase + c);
+    double lse = m + log(l);
+    if (J->lse_saved) lse = (double)J->lse_saved[(b * J->Hq + h) * S + i];
+    if (J->out_saved) {
+        for (int c = 0; c < J->d_v; ++c) o[c] = widen(J->out_saved, J->dtype, dobase + c);
+    } else {
+        for (int c = 0; c < J->d_v; ++c) o[c] = 0.0;
+        for (int64_t j = 0; j < S; ++j) {
+            if (score[j] == -INFINITY) continue;
+            const double p = exp(score[j] - lse);
+            const int64_t vbase = ((b * S + j) * J->Hkv + g) * J->v_row_stride;
+            for (int c = 0; c < J->d_v; ++c) o[c] += p * widen(J->v, J->dtype, vbase + c);
+        }
     }
     double D = 0.0;
     for (int c = 0; c < J->d_v; ++c) D += widen(J->dout, J->dtype, dobase + c) * o[c];
@@ -410,15 +422,18 @@ static void bwd_run(bwd_t *J, void *(*fn)(void *), int n_threads)
  *   k    [B, S, Hkv, k_row_stride]   v    [B, S, Hkv, v_row_stride]  (v may alias k, as in the forward)
  *   dq   [B, S, Hq, d_qk] fp64       dk   [B, S, Hkv, d_qk] fp64       dv [B, S, Hkv, d_v] fp64
  *   block = 0: token-granular pattern (n_sink, window in tokens); block > 0: sink blocks, local blocks.
+ *   out_saved, lse_saved: both NULL (recompute the forward), or what a forward pass stored.
  * Returns 0, -1 on a bad argument, -2 if a contributing row has no live key, -3 on allocation failure.
  */
 int oracle_ssa_backward(const void *q, const void *k, const void *v, const void *dout, int dtype,
                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                         int64_t k_row_stride, int64_t v_row_stride,
                         int64_t n_sink, int64_t window, int64_t block, double scale,
+                        const void *out_saved, const float *lse_saved,
                         double *dq, double *dk, double *dv, int n_threads)
 {
     if (!q || !k || !v || !dout || !dq || !dk || !dv) return -1;
+    if ((out_saved == NULL) != (lse_saved == NULL)) return -1;
     if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return -1;
     if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || d_qk < 1 || d_v < 1) return -1;
     if (k_row_stride < d_qk || v_row_stride < d_v || n_sink < 0 || window < 1 || block < 0) return -1;
@@ -442,6 +457,7 @@ int oracle_ssa_backward(const void *q, const void *k, const void *v, const void 
     J.d_qk = d_qk; J.d_v = d_v; J.k_row_stride = k_row_stride; J.v_row_stride = v_row_stride;
     J.n_sink = n_sink; J.window = window; J.block = block; J.scale = scale;
     J.n_rows = n_rows; J.rows = rows; J.dq = dq; J.dk = dk; J.dv = dv;
+    J.out_saved = out_saved; J.lse_saved = lse_saved;
     J.row_lse = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
     J.row_D = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
     if (!J.row_lse || !J.row_D) { free(rows); free(J.row_lse); free(J.row_D); return -3; }

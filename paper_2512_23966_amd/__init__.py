@@ -13,4 +13,6 @@ from .binding import (  # noqa: F401
     loza_ssa_decode_paged, loza_ssa_decode_paged_blocks,
     loza_ssa_prefill_calibration_blocks, loza_ssa_calibration_workspace_bytes,
     loza_ssa_extend, loza_ssa_extend_blocks, loza_ssa_extend_paged, loza_ssa_extend_paged_blocks,
+    loza_ssa_backward, loza_ssa_backward_blocks,
+    loza_ssa_backward_workspace_bytes, loza_ssa_backward_workspace_bytes_blocks,
 )

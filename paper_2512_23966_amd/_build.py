@@ -7,7 +7,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libloza_ssa.so"
-SOURCES = ["ssa_bf16.hip", "ssa_f32.hip", "ssa_api.hip"]
+SOURCES = ["ssa_bf16.hip", "ssa_bwd.hip", "ssa_f32.hip", "ssa_api.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instruction selection is switched off for every kernel of this library

@@ -29,6 +29,8 @@ EXPORTS = (
     "loza_ssa_decode_paged", "loza_ssa_decode_paged_blocks",
     "loza_ssa_prefill_calibration_blocks", "loza_ssa_calibration_workspace_bytes",
     "loza_ssa_extend", "loza_ssa_extend_blocks", "loza_ssa_extend_paged", "loza_ssa_extend_paged_blocks",
+    "loza_ssa_backward", "loza_ssa_backward_blocks",
+    "loza_ssa_backward_workspace_bytes", "loza_ssa_backward_workspace_bytes_blocks",
 )
 
 
@@ -88,6 +90,14 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_extend_paged.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_extend_paged_blocks.restype = ci
         L.loza_ssa_extend_paged_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, ci, ci, ci, i64, i64, i64, f32, vp]
+        L.loza_ssa_backward.restype = ci
+        L.loza_ssa_backward.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_backward_blocks.restype = ci
+        L.loza_ssa_backward_blocks.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_backward_workspace_bytes.restype = sz
+        L.loza_ssa_backward_workspace_bytes.argtypes = [ci, ci, ci, i64, ci, ci, i64, i64, ci]
+        L.loza_ssa_backward_workspace_bytes_blocks.restype = sz
+        L.loza_ssa_backward_workspace_bytes_blocks.argtypes = [ci, ci, ci, i64, ci, ci, i64, i64, i64, ci]
         L.loza_status_str.restype = ctypes.c_char_p
         L.loza_status_str.argtypes = [ci]
         _lib = L
@@ -365,3 +375,53 @@ def loza_ssa_extend_paged_blocks(q, k_pages, v_pages, block_table, seqlens, out,
     """Extend against a paged cache, block-granular pattern."""
     _extend_paged_common("loza_ssa_extend_paged_blocks", q, k_pages, v_pages, block_table, seqlens, out, lse,
                          (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
+
+
+def loza_ssa_backward_workspace_bytes(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, v_aliases_k) -> int:
+    return int(lib().loza_ssa_backward_workspace_bytes(B, Hq, Hkv, int(S), d_qk, d_v, int(n_sink), _win(window),
+                                                       1 if v_aliases_k else 0))
+
+
+def loza_ssa_backward_workspace_bytes_blocks(B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block,
+                                             v_aliases_k) -> int:
+    return int(lib().loza_ssa_backward_workspace_bytes_blocks(B, Hq, Hkv, int(S), d_qk, d_v, int(sink_blocks),
+                                                              _win(local_blocks), int(block), 1 if v_aliases_k else 0))
+
+
+def _backward_common(fn_name, q, k, v, out, lse, dout, dq, dk, dv, pattern, scale, workspace, stream):
+    """bf16 SSA backward. q, dq [B,S,Hq,d_qk]; k, dk [B,S,Hkv,d_qk]; v, dv [B,S,Hkv,d_v] (``v is k``:
+    dk receives the gradient of the shared tensor, dv is None); out, dout [B,S,Hq,d_v] bf16; lse
+    [B,Hq,S] fp32; workspace uint8 of at least ``loza_ssa_backward_workspace_bytes`` bytes."""
+    B, S, Hq, d_qk = q.shape
+    Hkv = k.shape[2]
+    d_v = out.shape[3]
+    if k.shape != (B, S, Hkv, d_qk) or out.shape != (B, S, Hq, d_v) or dout.shape != out.shape \
+            or lse.shape != (B, Hq, S) or dq.shape != q.shape or dk.shape != k.shape:
+        raise ValueError("shape mismatch between q, k, out, lse, dout, dq, dk")
+    bf = torch.bfloat16
+    kp = _dev_ptr(k, bf, "k")
+    if v is k:
+        vp, dvp = kp, None
+    else:
+        if v.shape != (B, S, Hkv, d_v) or dv is None or dv.shape != v.shape:
+            raise ValueError("v and dv must be [B, S, Hkv, d_v] (or v the very tensor passed as k)")
+        vp, dvp = _dev_ptr(v, bf, "v"), _dev_ptr(dv, bf, "dv")
+    rc = getattr(lib(), fn_name)(_dev_ptr(q, bf, "q"), kp, vp, _dev_ptr(out, bf, "out"), _dev_ptr(lse, torch.float32, "lse"),
+                                 _dev_ptr(dout, bf, "dout"), _dev_ptr(dq, bf, "dq"), _dev_ptr(dk, bf, "dk"), dvp,
+                                 B, Hq, Hkv, S, d_qk, d_v, *pattern, float(scale),
+                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_backward(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, scale, workspace, stream=None):
+    """Gradients of :func:`loza_ssa_prefill` (token-granular pattern); tensors as in :func:`_backward_common`."""
+    _backward_common("loza_ssa_backward", q, k, v, out, lse, dout, dq, dk, dv, (int(n_sink), _win(window)), scale,
+                     workspace, stream)
+
+
+def loza_ssa_backward_blocks(q, k, v, out, lse, dout, dq, dk, dv, sink_blocks, local_blocks, block, scale, workspace,
+                             stream=None):
+    """Gradients of :func:`loza_ssa_prefill_blocks` (block-granular pattern)."""
+    _backward_common("loza_ssa_backward_blocks", q, k, v, out, lse, dout, dq, dk, dv,
+                     (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)

@@ -357,6 +357,127 @@ int loza_ssa_prefill_blocks_f32(const float *q, const float *k, const float *v, 
     return prefill_f32(q, k, v, out, lse, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true, scale, stream);
 }
 
+// ---- backward ---------------------------------------------------------------------------------------
+
+// Host-side schedule of the key-stationary backward kernel: how many key tiles hold sink keys (their
+// rows run in chunks as workgroups of their own), how long a chunk is, how many the first tile has.
+static void backward_plan(loza::BwdParams &p)
+{
+    const int64_t n_kt = (p.S + 63) / 64;
+    const int64_t sink_kt = ((int64_t)p.n_sink + 63) / 64;
+    p.n_sink_kt = (int)(sink_kt < n_kt ? sink_kt : n_kt);
+    // a chunk is as long as the row range of a key tile without sink keys (64 keys + the window's reach)
+    const int64_t reach = (int64_t)p.window * p.block + 64 + p.block;
+    int64_t ct = ((reach < p.S ? reach : p.S) * p.G + 31) / 32 + 1;
+    if (ct < 64) ct = 64;
+    p.chunk_tiles = (int)ct;
+    int lo, hi;
+    loza::bwd_key_tile_rows(p, 0, lo, hi);
+    p.max_chunks = p.n_sink_kt > 0 ? (int)((hi - lo + 1 + ct - 1) / ct) : 1;
+}
+
+static int backward_fill(loza::BwdParams &p, int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                         int64_t sink, int64_t local, int64_t block, bool blocks, float scale, bool alias)
+{
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
+    if (!(scale > 0.f)) return LOZA_ERR_SHAPE;
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (!loza::bf16_shape_supported(d_qk, d_v, alias)) return LOZA_ERR_UNSUPPORTED;
+    if (!loza::bwd_group_supported(Hq / Hkv)) return LOZA_ERR_UNSUPPORTED;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv; p.S = S;
+    if (S * p.G > 2147483647LL - 64) return LOZA_ERR_SHAPE;
+    p.r_pad = (S * p.G + 31) / 32 * 32;
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S) : token_pattern(sink, local, S);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    backward_plan(p);
+    const int64_t n_kt = (S + 63) / 64;
+    const int64_t items = (int64_t)p.n_sink_kt * p.max_chunks + (n_kt - p.n_sink_kt);
+    if (items * Hkv * B > 2147483647LL || ((S * p.G + 63) / 64) * Hkv * B > 2147483647LL ||
+        ((int64_t)B * S * Hq + 3) / 4 > 2147483647LL)
+        return LOZA_ERR_SHAPE;
+    return LOZA_OK;
+}
+
+static size_t backward_bytes(const loza::BwdParams &p, int d_qk, int d_v, bool alias, size_t *part_offset)
+{
+    size_t stat = (size_t)p.B * p.Hkv * (size_t)p.r_pad * sizeof(float2);
+    stat = (stat + 255) / 256 * 256;
+    if (part_offset) *part_offset = stat;
+    const size_t cols = alias ? (size_t)d_qk : (size_t)d_qk + d_v;
+    const size_t part = p.max_chunks > 1 ? (size_t)p.B * p.Hkv * p.n_sink_kt * p.max_chunks * 64 * cols * sizeof(float) : 0;
+    return stat + part;
+}
+
+static size_t backward_workspace(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                 int64_t sink, int64_t local, int64_t block, bool blocks, int alias)
+{
+    loza::BwdParams p{};
+    if (backward_fill(p, B, Hq, Hkv, S, d_qk, d_v, sink, local, block, blocks, 1.0f, alias != 0) != LOZA_OK) return 0;
+    return backward_bytes(p, d_qk, d_v, alias != 0, nullptr);
+}
+
+static int backward_bf16(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                         const void *dout, void *dq, void *dk, void *dv,
+                         int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                         int64_t sink, int64_t local, int64_t block, bool blocks, float scale,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk) return LOZA_ERR_NULL;
+    const bool alias = (v == k);
+    if (!alias && !dv) return LOZA_ERR_NULL;
+    loza::BwdParams p{};
+    if (int rc = backward_fill(p, B, Hq, Hkv, S, d_qk, d_v, sink, local, block, blocks, scale, alias)) return rc;
+    size_t part_offset = 0;
+    const size_t need = backward_bytes(p, d_qk, d_v, alias, &part_offset);
+    if (!workspace || workspace_bytes < need) return LOZA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(dout) || !aligned16(dq) ||
+        !aligned16(dk) || (!alias && !aligned16(dv)) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return LOZA_ERR_ALIGN;
+    p.q = (const uint16_t *)q; p.k = (const uint16_t *)k; p.v = (const uint16_t *)v;
+    p.out = (const uint16_t *)out; p.dout = (const uint16_t *)dout; p.lse = lse;
+    p.dq = (uint16_t *)dq; p.dk = (uint16_t *)dk; p.dv = alias ? nullptr : (uint16_t *)dv;
+    p.rowstat = (float2 *)workspace;
+    p.part = (float *)((char *)workspace + part_offset);
+    return loza::launch_backward_bf16(p, d_qk, d_v, alias, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_backward(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                      const void *dout, void *dq, void *dk, void *dv,
+                      int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                      int64_t n_sink, int64_t window, float scale,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return backward_bf16(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, S, d_qk, d_v, n_sink, window, 1, false, scale,
+                         workspace, workspace_bytes, stream);
+}
+
+int loza_ssa_backward_blocks(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                             const void *dout, void *dq, void *dk, void *dv,
+                             int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                             int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    return backward_bf16(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block,
+                         true, scale, workspace, workspace_bytes, stream);
+}
+
+size_t loza_ssa_backward_workspace_bytes(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                         int64_t n_sink, int64_t window, int v_aliases_k)
+{
+    return backward_workspace(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, 1, false, v_aliases_k);
+}
+
+size_t loza_ssa_backward_workspace_bytes_blocks(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                                int64_t sink_blocks, int64_t local_blocks, int64_t block,
+                                                int v_aliases_k)
+{
+    if (check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return 0;
+    return backward_workspace(B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true, v_aliases_k);
+}
+
 int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window)
 {
     if (check_common(B, Hq, Hkv, S_max, 1, 1, n_sink, window, 1.0f) != LOZA_OK) return 0;

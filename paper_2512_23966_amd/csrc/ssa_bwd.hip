@@ -1,0 +1,553 @@
+// Backward of bf16 streaming sparse attention for gfx950 (MI355X): dQ, dK, dV over live tiles only.
+//
+// What is computed (the derivative of the paper's Eq. 4 that its sparse mid-training needs;
+// Architecture section, Training paragraph): with O = softmax(scale Q K*^T) V* over the live key set
+// of every query, lse the log of the softmax denominator and dO the gradient arriving at O,
+//   p_ij  = exp(scale q_i.k_j - lse_i)  (live j),   D_i = dO_i . O_i
+//   dV_j  = sum_i p_ij dO_i             dP_ij = dO_i . v_j        dS_ij = p_ij (dP_ij - D_i)
+//   dQ_i  = scale sum_j dS_ij k_j       dK_j  = scale sum_i dS_ij q_i
+// where the sums over i run over every query row (all heads of the key's group) that sees key j.
+// When the values are a prefix of the key rows (absorbed MLA: one latent serves both), the gradient
+// of that one tensor is dK with dV added to its first d_v columns, and that sum is what is written.
+//
+// Three kernels:
+//   * ssa_bwd_rowstat_kernel: per query row, (lse log2(e), D) in the row order the main kernel
+//     walks through (position-major, heads of a group together).
+//   * ssa_bwd_kernel<.., KEYS = false>: one workgroup keeps 64 query rows (Q and dO as matrix-core
+//     operands in registers) and streams the live key tiles of 32 keys past them: dQ.
+//   * ssa_bwd_kernel<.., KEYS = true>: one workgroup keeps 64 keys (K and V in registers) and
+//     streams the tiles of 32 query rows that see them: dK and dV. A key tile that holds sink keys
+//     is seen by every later query; its rows are cut into chunks that run as workgroups of their own
+//     and leave fp32 partial sums, which ssa_bwd_reduce_kernel adds in chunk order.
+// Both forms of the main kernel are the same program with the roles of rows and keys exchanged:
+//   stationary side X (two blocks of 32), streamed side Y (tiles of 32), and per tile
+//     phase 1:  S[y][x] = Y1 X1^T (contraction d_qk)   and   T[y][x] = Y2 X2^T (contraction d_v)
+//               on different wavefronts (S: waves 0, 1; T: waves 2, 3; one block of X each),
+//               T handed to the S waves through LDS, which form p and dS and leave them, as bf16,
+//               in LDS ([x][y], y contiguous);
+//     phase 2:  Acc^T[d][x] += Y^T[d][y] dS[y][x]  (and += Y2^T p for dV), all four waves, each
+//               owning one block of X and half of the column blocks; the streamed tile is read
+//               transposed from LDS (ds_read_b64_tr_b16) as the forward's value phase does.
+// The streamed tiles travel global -> LDS with global_load_lds_dwordx4 into a ring of two stages.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "ssa_device.h"
+#include "ssa_kernels.h"
+
+namespace loza {
+
+namespace {
+
+// One global -> LDS copy instruction: 64 lanes x 16 bytes from base + off (per lane) to the 1 KB of
+// LDS at lds_addr (wave-uniform, through M0). The compiler's wait counters do not see it: the tile
+// loop waits for all of them (vmcnt(0)) before the barrier that publishes a tile.
+__device__ __forceinline__ void copy_1k(const char *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n s_nop 0\n global_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+
+// Matrix-core A operand [32 columns of block db][16 items of key step ks] of a tile stored
+// [item][column] (padded rows of `row` bytes): two transposing 64-bit reads.
+__device__ __forceinline__ bf16x8 read_transposed(const char *tile, int row, int db, int ks, int lane)
+{
+    const int lh = lane >> 5, s16 = lane & 15, g16 = (lane >> 4) & 1;
+    const char *a = tile + (ks * 16 + lh * 8 + (s16 >> 2)) * row + (db * 32 + g16 * 16 + (s16 & 3) * 4) * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a + 4 * row));
+    s16x8 a8;
+    a8[0] = lo[0]; a8[1] = lo[1]; a8[2] = lo[2]; a8[3] = lo[3];
+    a8[4] = hi[0]; a8[5] = hi[1]; a8[6] = hi[2]; a8[7] = hi[3];
+    return __builtin_bit_cast(bf16x8, a8);
+}
+
+}  // namespace
+
+// (lse log2(e), dO . O) of every query row, stored [B, Hkv, Rpad] with row index i * G + head-in-group.
+template <int DV>
+__global__ __launch_bounds__(256) void ssa_bwd_rowstat_kernel(const BwdParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // flat (b, i, h)
+    const int64_t n_rows = (int64_t)p.B * p.S * p.Hq;
+    if (row >= n_rows) return;
+    const uint16_t *o = p.out + row * DV, *d = p.dout + row * DV;
+    float acc = 0.f;
+    for (int c = lane * 8; c < DV; c += 512) {
+        const u32x4 a = *(const u32x4 *)(o + c), b = *(const u32x4 *)(d + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = __builtin_fmaf(__builtin_bit_cast(float, a[e] << 16), __builtin_bit_cast(float, b[e] << 16), acc);
+            acc = __builtin_fmaf(__builtin_bit_cast(float, a[e] & 0xffff0000u), __builtin_bit_cast(float, b[e] & 0xffff0000u), acc);
+        }
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s, 64);
+    if (lane == 0) {
+        const int h = (int)(row % p.Hq);
+        const int64_t bi = row / p.Hq, i = bi % p.S, b = bi / p.S;
+        const int g = h / p.G, hh = h - g * p.G;
+        float2 st;
+        st.x = p.lse[(b * p.Hq + h) * p.S + i] * 1.44269504088896340736f;
+        st.y = acc;
+        p.rowstat[(b * p.Hkv + g) * p.r_pad + i * p.G + hh] = st;
+    }
+}
+
+template <int DQK, int DV, bool ALIAS, bool KEYS>
+struct BwdCfg {
+    static constexpr int ROW1 = DQK * 2 + 16, ROW2 = DV * 2 + 16;   // padded LDS rows of the streamed tiles
+    static constexpr int CPR1 = ROW1 / 16, CPR2 = ROW2 / 16;
+    static constexpr bool HAS_Y2 = KEYS || !ALIAS;    // a second streamed tile (dO rows, or separate values)
+    static constexpr int N1 = (32 * CPR1 + 63) / 64;  // 1 KB copy instructions per tile
+    static constexpr int N2 = HAS_Y2 ? (32 * CPR2 + 63) / 64 : 0;
+    static constexpr int NSTAT = KEYS ? 1 : 0;        // + the row statistics of the tile
+    static constexpr int NI = N1 + N2 + NSTAT;
+    static constexpr int PER_WAVE = (NI + 3) / 4;
+    static constexpr int STAGE = NI * 1024;
+    static constexpr int OFF_Y2 = N1 * 1024, OFF_STAT = (N1 + N2) * 1024;
+    static constexpr int PROW = 32 * 2 + 16;          // LDS bytes per row of the dS / p buffers
+    static constexpr int XREGION = 2 * 32 * PROW;     // per block of X: dS rows, then p rows (also the T hand-over)
+    static_assert(XREGION >= 64 * 16 * 4, "the T hand-over must fit the region it shares");
+    static constexpr int OFF_BUF = 2 * STAGE;
+    static constexpr int LDS_BYTES = OFF_BUF + 2 * XREGION;
+    static_assert(LDS_BYTES <= 160 * 1024, "does not fit the 160 KB LDS");
+    // accumulator blocks (32 columns x 32 items of X) per wave
+    static constexpr bool SPLIT_KV = KEYS && !ALIAS;  // half the waves take dK, the other half dV
+    static_assert(!SPLIT_KV || DQK == DV, "separate values: equal widths only");
+    static constexpr int NACC = SPLIT_KV ? DQK / 32 : DQK / 64;
+    static_assert(DQK % 64 == 0 && DV % 32 == 0 && DV <= DQK, "head widths");
+};
+
+template <int DQK, int DV, bool ALIAS, bool KEYS>
+__global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
+{
+    using C = BwdCfg<DQK, DV, ALIAS, KEYS>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+    const int xb = wave & 1, role = wave >> 1;  // role 0: S = Y1 X1^T and the elementwise step; role 1: T = Y2 X2^T
+    const int G = p.G;
+    const int64_t S = p.S, R = S * G;
+    const int n_sink = p.n_sink, window = p.window, block = p.block;
+
+    // ---- which work item ----------------------------------------------------------------------------
+    int b, g, xt, chunk = 0;
+    bool partial = false;  // KEYS: leave an fp32 partial sum for the reduce kernel
+    if (!KEYS) {
+        const int x_tiles = (int)((R + 63) / 64);
+        int id = blockIdx.x;
+        xt = x_tiles - 1 - id % x_tiles;  // latest (heaviest) rows first
+        id /= x_tiles;
+        g = id % p.Hkv;
+        b = id / p.Hkv;
+    } else {
+        const int n_kt = (int)((S + 63) / 64);
+        const int items = p.n_sink_kt * p.max_chunks + (n_kt - p.n_sink_kt);
+        int id = blockIdx.x;
+        const int it = id % items;
+        id /= items;
+        g = id % p.Hkv;
+        b = id / p.Hkv;
+        if (it < p.n_sink_kt * p.max_chunks) {
+            xt = it / p.max_chunks;
+            chunk = it % p.max_chunks;
+            partial = p.max_chunks > 1;
+        } else {
+            xt = p.n_sink_kt + (it - p.n_sink_kt * p.max_chunks);
+        }
+    }
+
+    // ---- streamed tiles of this item -------------------------------------------------------------
+    // !KEYS: the live key tiles of rows [xt*64, xt*64+64): sink tiles [0, nA), then window tiles.
+    // KEYS: the row tiles [yt_begin, yt_begin + nt) that can see keys [xt*64, xt*64+64).
+    int nt, nA = 0, wt0 = 0, yt_begin = 0;
+    int i_min = 0, i_max = 0, w_lo_max = 0;
+    if (!KEYS) {
+        const int64_t r_last = (int64_t)xt * 64 + 63 < R ? (int64_t)xt * 64 + 63 : R - 1;
+        i_min = (int)(((int64_t)xt * 64) / G);
+        i_max = (int)(r_last / G);
+        const int sink_end = n_sink < i_max + 1 ? n_sink : i_max + 1;
+        const int win_begin = window_begin_of(i_min, window, block);
+        w_lo_max = window_begin_of(i_max, window, block);
+        nA = (sink_end + 31) / 32;
+        wt0 = win_begin / 32;
+        const int wt1 = i_max / 32;
+        int nB;
+        if (wt0 <= nA) { nA = wt1 + 1; nB = 0; } else { nB = wt1 - wt0 + 1; }
+        nt = nA + nB;
+    } else {
+        int yt_lo, yt_hi;
+        bwd_key_tile_rows(p, xt, yt_lo, yt_hi);
+        yt_begin = yt_lo;
+        int yt_end = yt_hi + 1;
+        if (xt < p.n_sink_kt) {
+            yt_begin = yt_lo + chunk * p.chunk_tiles;
+            if (yt_begin + p.chunk_tiles < yt_end) yt_end = yt_begin + p.chunk_tiles;
+        }
+        nt = yt_end - yt_begin;
+        if (nt <= 0) return;  // a chunk beyond the rows of this key tile (the reduce kernel knows)
+    }
+    auto y_tile = [&](int t) { return KEYS ? yt_begin + t : (t < nA ? t : wt0 + (t - nA)); };
+
+    // ---- the stationary side: matrix-core B operands in registers --------------------------------
+    constexpr int NKK = DQK / 16;
+    bf16x8 xf[NKK];
+    const int64_t x_idx = (int64_t)xt * 64 + xb * 32 + ln;          // row (i * G + head) or key
+    const int64_t x_c = x_idx < (KEYS ? S : R) ? x_idx : (KEYS ? S : R) - 1;
+    int x_i = 0;                                                     // !KEYS: position of this lane's row
+    float x_lse2 = 0.f, x_D = 0.f;
+    {
+        const uint16_t *xp;
+        if (!KEYS) {
+            const int64_t i = x_c / G;
+            const int hh = (int)(x_c - i * G);
+            x_i = (int)i;
+            const int64_t qrow = (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh);
+            xp = role == 0 ? p.q + qrow * DQK : p.dout + qrow * DV;
+            const float2 st = p.rowstat[((int64_t)b * p.Hkv + g) * p.r_pad + x_c];
+            x_lse2 = st.x;
+            x_D = st.y;
+        } else {
+            const int64_t krow = ((int64_t)b * S + x_c) * p.Hkv + g;
+            xp = role == 0 ? p.k + krow * DQK : p.v + krow * (ALIAS ? DQK : DV);
+        }
+        xp += lh * 8;
+        // (two loops with constant bounds: a bound that depends on the role would turn every
+        // matrix instruction below into a predicated one)
+        if (role == 0) {
+#pragma unroll
+            for (int kk = 0; kk < DQK / 16; ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < DV / 16; ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
+        }
+    }
+    const int w_lo_row = KEYS ? 0 : window_begin_of(x_i, window, block);
+
+    // ---- global -> LDS copy plan of a streamed tile (the same for every tile) ---------------------
+    // Instruction n fills LDS bytes [n*1024, n*1024 + 1024) of the stage: slot n*64 + lane of the
+    // padded tile it belongs to is chunk (slot % CPR) of item (slot / CPR). The padding chunk of a row
+    // and the slots past the tile fetch a valid chunk that nobody reads back; items past the end of
+    // the tensor are cut to the last valid one by clamping the offset (offsets grow with the item).
+    const int64_t pos_stride = KEYS ? (int64_t)p.Hq : (int64_t)p.Hkv;   // rows between consecutive positions
+    auto item_offset = [&](int item, int width) -> uint32_t {           // byte offset of a tile item, row width in elements
+        if (!KEYS) return (uint32_t)((int64_t)item * pos_stride * width * 2);
+        if (G >= 32) return (uint32_t)(item * width * 2);               // 32 heads of one position
+        return (uint32_t)(((int64_t)(item / G) * pos_stride + item % G) * width * 2);
+    };
+    constexpr int W2 = (!KEYS && ALIAS) ? DQK : DV;                      // element width of a Y2 row in memory
+    uint32_t yoff[C::PER_WAVE];
+#pragma unroll
+    for (int u = 0; u < C::PER_WAVE; ++u) {
+        const int n = u * 4 + wave;
+        if (n < C::N1) {
+            const int slot = n * 64 + lane, item = slot / C::CPR1 < 31 ? slot / C::CPR1 : 31;
+            const int c = slot % C::CPR1 < C::CPR1 - 2 ? slot % C::CPR1 : C::CPR1 - 2;
+            yoff[u] = item_offset(item, DQK) + c * 16;
+        } else if (n < C::N1 + C::N2) {
+            const int slot = (n - C::N1) * 64 + lane, item = slot / C::CPR2 < 31 ? slot / C::CPR2 : 31;
+            const int c = slot % C::CPR2 < C::CPR2 - 2 ? slot % C::CPR2 : C::CPR2 - 2;
+            yoff[u] = item_offset(item, W2) + c * 16;
+        } else {
+            yoff[u] = (lane < 15 ? lane : 15) * 16;  // 32 rows x 8 bytes of statistics
+        }
+    }
+    const char *y1_all = KEYS ? (const char *)p.q : (const char *)p.k;
+    const char *y2_all = KEYS ? (const char *)p.dout : (const char *)p.v;
+    auto issue_tile = [&](int t, int stage) {
+        const int64_t y0 = (int64_t)y_tile(t) * 32;                  // first row / key of the tile
+        const int64_t y_left = (KEYS ? R : S) - 1 - y0;
+        const int lim = y_left < 31 ? (int)y_left : 31;              // last valid item of the tile
+        int64_t row0;                                                // tensor row (of d elements) the tile starts at
+        if (KEYS) {
+            const int64_t i0 = y0 / G;
+            const int hh0 = (int)(y0 - i0 * G);
+            row0 = ((int64_t)b * S + i0) * p.Hq + (int64_t)g * G + hh0;
+        } else {
+            row0 = ((int64_t)b * S + y0) * p.Hkv + g;
+        }
+        const char *b1 = y1_all + row0 * DQK * 2;
+        const char *b2 = y2_all + row0 * W2 * 2;
+        const char *b3 = (const char *)(p.rowstat + ((int64_t)b * p.Hkv + g) * p.r_pad + y0);
+        const uint32_t max1 = item_offset(lim, DQK) + (C::CPR1 - 2) * 16;
+        const uint32_t max2 = item_offset(lim, W2) + (C::CPR2 - 2) * 16;
+        const uint32_t dst = smem_lds + stage * C::STAGE;
+#pragma unroll
+        for (int u = 0; u < C::PER_WAVE; ++u) {
+            const int n = u * 4 + wave;  // wave-uniform
+            if (n < C::N1) copy_1k(b1, yoff[u] < max1 ? yoff[u] : max1, dst + n * 1024);
+            else if (n < C::N1 + C::N2) copy_1k(b2, yoff[u] < max2 ? yoff[u] : max2, dst + n * 1024);
+            else if (n < C::NI) copy_1k(b3, yoff[u], dst + n * 1024);
+        }
+    };
+
+    f32x16 acc[C::NACC];
+#pragma unroll
+    for (int a = 0; a < C::NACC; ++a)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
+
+    char *region = smem + C::OFF_BUF + xb * C::XREGION;   // dS rows of this block of X, then its p rows
+    const int j_min_x = xt * 64, j_max_x = xt * 64 + 63;   // KEYS: the keys of this workgroup
+
+    issue_tile(0, 0);
+    for (int u = 0; u < nt; ++u) {
+        const int st = u & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
+        __syncthreads();                                  // ... everyone's; tile u - 1 is no longer read
+        if (u + 1 < nt) issue_tile(u + 1, st ^ 1);
+        const char *tile = smem + st * C::STAGE;
+
+        // ---- phase 1: one 32 x 32 block of S or T ---------------------------------------------------
+        f32x16 c;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c[e] = 0.f;
+        if (role == 0) {
+            const char *ya = tile + ln * C::ROW1 + lh * 16;
+#pragma unroll
+            for (int kk = 0; kk < DQK / 16; ++kk)
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ya + kk * 32), xf[kk], c, 0, 0, 0);
+        } else {
+            // T reads the second streamed tile when there is one (else the values are the key rows' prefix)
+            const char *ya = tile + (C::HAS_Y2 ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16;
+#pragma unroll
+            for (int kk = 0; kk < DV / 16; ++kk)
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ya + kk * 32), xf[kk], c, 0, 0, 0);
+        }
+        if (role == 1) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                float4 w;
+                w.x = c[4 * qd]; w.y = c[4 * qd + 1]; w.z = c[4 * qd + 2]; w.w = c[4 * qd + 3];
+                *(float4 *)(region + (qd * 64 + lane) * 16) = w;
+            }
+        }
+        __syncthreads();
+
+        // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
+        if (role == 0) {
+            float tt[16];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const float4 w = *(const float4 *)(region + (qd * 64 + lane) * 16);
+                tt[4 * qd] = w.x; tt[4 * qd + 1] = w.y; tt[4 * qd + 2] = w.z; tt[4 * qd + 3] = w.w;
+            }
+            const int y0 = y_tile(u) * 32;
+            float pv[16], dsv[16];
+            if (!KEYS) {
+                // lane = query row, elements = keys y0 + 8 (e >> 2) + 4 lh + (e & 3)
+                const bool interior = (y0 + 31 <= i_min) && ((y0 + 31 < n_sink) || (y0 >= w_lo_max));
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int j = y0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                    const bool ok = interior || ((j <= x_i) & ((j < n_sink) | (j >= w_lo_row)));
+                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -x_lse2));
+                    pv[e] = ok ? pe : 0.f;
+                    dsv[e] = ok ? p.scale * pe * (tt[e] - x_D) : 0.f;
+                }
+            } else {
+                // lane = key, elements = query rows y0 + 8 (e >> 2) + 4 lh + (e & 3)
+                const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
+                const int i_lo = (int)((int64_t)y0 / G), i_hi = (int)(((int64_t)y0 + 31) / G);
+                const bool interior = ((int64_t)y0 + 31 < R) && (j_max_x < S) && (j_max_x <= i_lo) &&
+                                      ((j_max_x < n_sink) || (j_min_x >= window_begin_of(i_hi, window, block)));
+                const int j = (int)x_idx;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int y = 8 * (e >> 2) + 4 * lh + (e & 3);
+                    const float2 sd = stat[y];
+                    bool ok = true;
+                    if (!interior) {
+                        const int64_t r = (int64_t)y0 + y;
+                        const int i = (int)(r / G);
+                        ok = (r < R) & (j < S) & (j <= i) & ((j < n_sink) | (j >= window_begin_of(i, window, block)));
+                    }
+                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -sd.x));
+                    pv[e] = ok ? pe : 0.f;
+                    dsv[e] = ok ? p.scale * pe * (tt[e] - sd.y) : 0.f;
+                }
+            }
+            // [x][y] with y contiguous: this lane's 16 values are four runs of four consecutive y
+            char *ps = region + ln * C::PROW + (4 * lh) * 2;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                u32x2 w;
+                w[0] = pack_bf16(dsv[4 * qd], dsv[4 * qd + 1]);
+                w[1] = pack_bf16(dsv[4 * qd + 2], dsv[4 * qd + 3]);
+                *(u32x2 *)(ps + qd * 16) = w;
+                if (KEYS) {
+                    w[0] = pack_bf16(pv[4 * qd], pv[4 * qd + 1]);
+                    w[1] = pack_bf16(pv[4 * qd + 2], pv[4 * qd + 3]);
+                    *(u32x2 *)(ps + 32 * C::PROW + qd * 16) = w;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- phase 2: Acc^T[column block][x] += Y^T dS (+ Y2^T p) -----------------------------------
+        {
+            const char *bs = region + ln * C::PROW + lh * 16;
+            const char *t1 = tile, *t2 = tile + C::OFF_Y2;
+            auto phase2 = [&](auto half) {
+                constexpr int HF = decltype(half)::value;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const bf16x8 b_ds = *(const bf16x8 *)(bs + ks * 32);
+                    bf16x8 b_p = b_ds;
+                    if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW + ks * 32);
+#pragma unroll
+                    for (int a = 0; a < C::NACC; ++a) {
+                        if (C::SPLIT_KV) {
+                            if (HF == 0) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t1, C::ROW1, a, ks, lane), b_ds, acc[a], 0, 0, 0);
+                            else acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t2, C::ROW2, a, ks, lane), b_p, acc[a], 0, 0, 0);
+                        } else {
+                            constexpr int DB0 = HF * C::NACC;
+                            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t1, C::ROW1, DB0 + a, ks, lane), b_ds, acc[a], 0, 0, 0);
+                            if (KEYS && DB0 + a < DV / 32)
+                                acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t2, C::ROW2, DB0 + a, ks, lane), b_p, acc[a], 0, 0, 0);
+                        }
+                    }
+                }
+            };
+            if (role == 0) phase2(std::integral_constant<int, 0>{});
+            else phase2(std::integral_constant<int, 1>{});
+        }
+    }
+
+    // ---- epilogue: lane = item of X, 16 values of a block = four runs of four consecutive columns ------
+    if (x_idx >= (KEYS ? S : R)) return;
+    const int hf = role;
+    if (!KEYS) {
+        const int64_t i = x_idx / G;
+        const int hh = (int)(x_idx - i * G);
+        uint16_t *op = p.dq + (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh) * DQK + hf * C::NACC * 32 + 4 * lh;
+#pragma unroll
+        for (int a = 0; a < C::NACC; ++a)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                u32x2 w;
+                w[0] = pack_bf16(acc[a][4 * qd], acc[a][4 * qd + 1]);
+                w[1] = pack_bf16(acc[a][4 * qd + 2], acc[a][4 * qd + 3]);
+                *(u32x2 *)(op + a * 32 + qd * 8) = w;
+            }
+    } else {
+        // column of the first accumulator block of this wave in the row [dK (d_qk) | dV (d_v, separate values only)]
+        const int col0 = C::SPLIT_KV ? hf * DQK : hf * C::NACC * 32;
+        if (partial) {
+            constexpr int COLS = C::SPLIT_KV ? DQK + DV : DQK;
+            float *op = p.part + ((((int64_t)b * p.Hkv + g) * p.n_sink_kt + xt) * p.max_chunks + chunk) * 64 * COLS +
+                        (int64_t)(xb * 32 + ln) * COLS + col0 + 4 * lh;
+#pragma unroll
+            for (int a = 0; a < C::NACC; ++a)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    float4 w;
+                    w.x = acc[a][4 * qd]; w.y = acc[a][4 * qd + 1]; w.z = acc[a][4 * qd + 2]; w.w = acc[a][4 * qd + 3];
+                    *(float4 *)(op + a * 32 + qd * 8) = w;
+                }
+        } else {
+            const int64_t krow = ((int64_t)b * S + x_idx) * p.Hkv + g;
+            uint16_t *op = (C::SPLIT_KV && hf == 1) ? p.dv + krow * DV + 4 * lh : p.dk + krow * DQK + col0 + 4 * lh;
+#pragma unroll
+            for (int a = 0; a < C::NACC; ++a)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][4 * qd], acc[a][4 * qd + 1]);
+                    w[1] = pack_bf16(acc[a][4 * qd + 2], acc[a][4 * qd + 3]);
+                    *(u32x2 *)(op + a * 32 + qd * 8) = w;
+                }
+        }
+    }
+}
+
+// Sum of the chunk partials of the key tiles that hold sink keys, in chunk order, rounded once.
+// One thread per four columns of one key.
+template <int DQK, int DV, bool ALIAS>
+__global__ __launch_bounds__(256) void ssa_bwd_reduce_kernel(const BwdParams p)
+{
+    constexpr int COLS = ALIAS ? DQK : DQK + DV;
+    constexpr int TPK = COLS / 4;  // threads per key
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t n_keys = (int64_t)p.B * p.Hkv * p.n_sink_kt * 64;
+    if (t >= n_keys * TPK) return;
+    const int c = (int)(t % TPK) * 4;
+    const int64_t key = t / TPK;
+    const int x = (int)(key % 64);
+    const int64_t tile = key / 64;  // flat (b, g, kt)
+    const int kt = (int)(tile % p.n_sink_kt);
+    const int64_t bg = tile / p.n_sink_kt;
+    const int g = (int)(bg % p.Hkv);
+    const int64_t b = bg / p.Hkv;
+    const int64_t j = (int64_t)kt * 64 + x;
+    if (j >= p.S) return;
+    int yt_lo, yt_hi;
+    bwd_key_tile_rows(p, kt, yt_lo, yt_hi);
+    const int chunks = (yt_hi - yt_lo + 1 + p.chunk_tiles - 1) / p.chunk_tiles;
+    float4 s = {0.f, 0.f, 0.f, 0.f};
+    const float *pp = p.part + (tile * p.max_chunks * 64 + x) * COLS + c;
+    for (int ch = 0; ch < chunks; ++ch) {
+        const float4 v = *(const float4 *)(pp + (int64_t)ch * 64 * COLS);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    u32x2 w;
+    w[0] = pack_bf16(s.x, s.y);
+    w[1] = pack_bf16(s.z, s.w);
+    const int64_t krow = (b * p.S + j) * p.Hkv + g;
+    if (c < DQK) *(u32x2 *)(p.dk + krow * DQK + c) = w;
+    else *(u32x2 *)(p.dv + krow * DV + (c - DQK)) = w;
+}
+
+template <int DQK, int DV, bool ALIAS>
+static hipError_t launch_backward_t(const BwdParams &p, hipStream_t stream)
+{
+    const int64_t n_rows = (int64_t)p.B * p.S * p.Hq;
+    hipLaunchKernelGGL((ssa_bwd_rowstat_kernel<DV>), dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    {
+        using C = BwdCfg<DQK, DV, ALIAS, false>;
+        auto kern = ssa_bwd_kernel<DQK, DV, ALIAS, false>;
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        const int64_t blocks = ((p.S * p.G + 63) / 64) * p.Hkv * p.B;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    {
+        using C = BwdCfg<DQK, DV, ALIAS, true>;
+        auto kern = ssa_bwd_kernel<DQK, DV, ALIAS, true>;
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        const int64_t n_kt = (p.S + 63) / 64;
+        const int64_t blocks = ((int64_t)p.n_sink_kt * p.max_chunks + (n_kt - p.n_sink_kt)) * p.Hkv * p.B;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    if (p.n_sink_kt > 0 && p.max_chunks > 1) {
+        constexpr int COLS = ALIAS ? DQK : DQK + DV;
+        const int64_t threads = (int64_t)p.B * p.Hkv * p.n_sink_kt * 64 * (COLS / 4);
+        hipLaunchKernelGGL((ssa_bwd_reduce_kernel<DQK, DV, ALIAS>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// The row tiles of the key-stationary kernel must not straddle positions unevenly: heads per group a
+// power of two up to 32 (a tile is 32 / G whole positions) or a multiple of 32 (a tile is part of one).
+bool bwd_group_supported(int G) { return G >= 1 && (G % 32 == 0 || (G < 32 && (G & (G - 1)) == 0)); }
+
+hipError_t launch_backward_bf16(const BwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream)
+{
+    if (d_qk == 576 && d_v == 512 && alias) return launch_backward_t<576, 512, true>(p, stream);
+    if (d_qk == 128 && d_v == 128) return alias ? launch_backward_t<128, 128, true>(p, stream)
+                                                : launch_backward_t<128, 128, false>(p, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace loza

@@ -47,6 +47,42 @@ hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias,
 hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float alpha, uint16_t *out,
                              uint16_t *out_full, uint16_t *out_sparse, int64_t n, hipStream_t stream);
 
+// Arguments of the bf16 backward kernels. Pattern fields as in FwdParams.
+struct BwdParams {
+    const uint16_t *q, *k, *v, *out, *dout;
+    const float *lse;
+    uint16_t *dq, *dk, *dv;   // dv is unused when v aliases k (dk then holds the gradient of the shared tensor)
+    float2 *rowstat;          // workspace: [B, Hkv, r_pad] (lse * log2(e), dO . O), row index i * G + head-in-group
+    float *part;              // workspace: [B, Hkv, n_sink_kt, max_chunks, 64, columns] fp32 partial dK | dV
+    int B, Hq, Hkv, G;
+    int64_t S;
+    int64_t r_pad;            // S * G rounded up to a multiple of 32
+    int n_sink, window, block;
+    float scale, scale_log2;
+    int n_sink_kt;            // key tiles (of 64 keys) that hold at least one sink key
+    int chunk_tiles;          // row tiles (of 32 rows) per chunk of such a key tile
+    int max_chunks;           // chunks of the first key tile (the one with most rows)
+};
+
+// Row tiles (32 rows each, row = position * G + head-in-group) that can see a key of key tile kt
+// (64 keys): from the tile's first key on (causality) to the last position whose window still holds
+// the tile's last key, or to the end of the sequence if the tile holds a sink key.
+__host__ __device__ inline void bwd_key_tile_rows(const BwdParams &p, int kt, int &yt_lo, int &yt_hi)
+{
+    const int64_t j0 = (int64_t)kt * 64;
+    const int64_t j1 = j0 + 63 < p.S ? j0 + 63 : p.S - 1;
+    int64_t i_hi = p.S - 1;
+    if (j0 >= p.n_sink) {
+        const int64_t last = (j1 / p.block + p.window) * p.block - 1;  // window <= S: no overflow
+        if (last < i_hi) i_hi = last;
+    }
+    yt_lo = (int)((j0 * p.G) / 32);
+    yt_hi = (int)(((i_hi + 1) * p.G - 1) / 32);
+}
+
+bool bwd_group_supported(int G);
+hipError_t launch_backward_bf16(const BwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
+
 struct F32Params {
     const float *q, *k, *v;
     float *out, *lse;

@@ -126,3 +126,86 @@ def compare_decode(q, kc, vc, seqlens, out, lse, rb, rh, n_sink, window, scale, 
     got_lse = lse[torch.as_tensor(rb, device=dev), torch.as_tensor(rh, device=dev)].double().cpu().numpy()
     assert np.isfinite(got_out).all(), f"{label}: non-finite output"
     return _judge(got_out, ref_out, got_lse, ref_lse, torch.bfloat16, len(rb), label)
+
+
+# ---- backward -------------------------------------------------------------------------------------
+
+def oracle_forward_all(q, k, v, n_sink, window, scale, d_v, block=None):
+    """Oracle forward of every row, shaped like the tensors the backward takes: out [B,S,Hq,d_v]
+    rounded to bf16 (what a forward pass hands to the backward), lse [B,Hq,S] fp32."""
+    B, S, Hq, _ = q.shape
+    rb, rh, ri = all_rows(B, Hq, S)
+    out, lse = oracle_prefill_rows(q, k, v, rb, rh, ri, n_sink, window, scale, d_v, block)
+    out_t = torch.zeros(B, S, Hq, d_v, dtype=torch.float64)
+    out_t[torch.as_tensor(rb), torch.as_tensor(ri), torch.as_tensor(rh)] = torch.as_tensor(out)
+    lse_t = torch.zeros(B, Hq, S, dtype=torch.float64)
+    lse_t[torch.as_tensor(rb), torch.as_tensor(rh), torch.as_tensor(ri)] = torch.as_tensor(lse)
+    return out_t.to(torch.bfloat16).to(q.device), lse_t.to(torch.float32).to(q.device)
+
+
+def run_backward(q, k, v, out, lse, dout, n_sink, window, scale, block=None):
+    """HIP backward through the C ABI. Returns (dq, dk, dv); with ``v is k`` dk is the gradient of the
+    shared tensor and dv is None. The outputs start as NaN: every element must be written."""
+    B, S, Hq, d_qk = q.shape
+    Hkv, d_v = k.shape[2], out.shape[3]
+    alias = v is k
+    nan = float("nan")
+    dq = torch.full_like(q, nan)
+    dk = torch.full_like(k, nan)
+    dv = None if alias else torch.full_like(v, nan)
+    if block is None:
+        nb = loza.loza_ssa_backward_workspace_bytes(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, alias)
+        ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=q.device)
+        loza.loza_ssa_backward(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, scale, ws)
+    else:
+        nb = loza.loza_ssa_backward_workspace_bytes_blocks(B, Hq, Hkv, S, d_qk, d_v, n_sink, window, block, alias)
+        ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=q.device)
+        loza.loza_ssa_backward_blocks(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, block, scale, ws)
+    torch.cuda.synchronize()
+    return dq, dk, dv
+
+
+# Bound on a gradient element. Every element of a gradient row is a sum of products (weight x vector
+# element) whose weights (p, dS) reach the matrix cores rounded to bf16 (relative error 2^-9 each, of
+# random sign), so its error is a random sum of the same size as 2^-9 times the root-sum-square of
+# the terms -- which is also the typical size of the elements of that row, whether or not the
+# element itself happens to be small by cancellation. The bound is therefore GRAD_K of those units
+# (rms of the reference row times 2^-9), GRAD_K covering the several rounded factors (p, dS, the
+# bf16 `out` inside D) and the maximum over millions of elements, plus the rounding of the result,
+# plus a floor for rows whose gradient vanishes by cancellation (a query with one live key has
+# dP = D exactly; the kernel forms the two 512-term dot products in fp32 in different orders).
+GRAD_K = 16.0
+GRAD_FLOOR = 2e-5
+
+
+def grad_tolerance(ref: np.ndarray) -> np.ndarray:
+    row_rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    return GRAD_K * 2.0 ** -9 * row_rms + 2.0 ** -9 * np.abs(ref) + GRAD_FLOOR
+
+
+def compare_backward(q, k, v, out, lse, dout, got, n_sink, window, scale, label="", block=None):
+    """Element by element against the oracle's gradient taken from the same stored out and lse."""
+    dq, dk, dv = got
+    d_v = dout.shape[3]
+    alias = v is k
+    w = oracle.INT64_MAX if window is None else window
+    varg = ("alias", d_v) if alias else v.cpu()
+    rq, rk, rv = oracle.ssa_backward(q.cpu(), k.cpu(), varg, dout.cpu(), n_sink=n_sink, window=w, scale=scale, block=block,
+                                     out=out.cpu(), lse=lse.cpu())
+    if alias:
+        rk = rk.copy()
+        rk[..., :d_v] += rv
+    pairs = [("dq", dq, rq), ("dk", dk, rk)] + ([] if alias else [("dv", dv, rv)])
+    worst = {}
+    for name, g, r in pairs:
+        gg = g.double().cpu().numpy()
+        assert np.isfinite(gg).all(), f"{label}: {name} has non-finite or unwritten elements"
+        err = np.abs(gg - r)
+        over = float((err - grad_tolerance(r)).max())
+        worst[name] = float(err.max())
+        unit = 2.0 ** -9 * np.sqrt((r ** 2).mean(axis=-1, keepdims=True)) + GRAD_FLOOR
+        print(f"[parity] {label}: {name} max|err|={err.max():.3e} max|ref|={np.abs(r).max():.3e} "
+              f"rms err={np.sqrt((err ** 2).mean()):.3e} max err in units of 2^-9 row rms={(err / unit).max():.2f} "
+              f"(bound {GRAD_K})", flush=True)
+        assert over <= 0.0, f"{label}: {name} error exceeds its bound by {over} (max error {err.max()})"
+    return worst

@@ -157,6 +157,37 @@ def test_rows_without_dout_contribute_nothing_and_get_zero_dq():
     assert np.abs(dq[0, :7]).max() == 0.0 and np.count_nonzero(np.abs(dq).sum(-1)) == 2
 
 
+def test_saved_forward_of_its_own_gives_the_gradient_and_the_substitution_is_the_stated_one():
+    """With the forward's own out and lse handed in, nothing changes (up to their fp32 storage); with
+    other values, D_i = dO_i . out_i and p_ij = exp(scale q_i.k_j - lse_i) are what enter: checked on
+    dV, which is sum_i p_ij dO_i and so scales by exp(-shift) when every lse is shifted, and on dQ
+    through the closed form for one query row."""
+    B, S, Hq, d, dv, ns, win, scale = 1, 30, 2, 6, 5, 2, 7, 0.5
+    q, k, v, dout = _rand((B, S, Hq, d), 61), _rand((B, S, 1, d), 62), _rand((B, S, 1, dv), 63), _rand((B, S, Hq, dv), 64)
+    b, i, h = np.meshgrid(np.arange(B), np.arange(S), np.arange(Hq), indexing="ij")
+    rb, ri, rh = b.ravel(), i.ravel(), h.ravel()
+    qr = q[torch.as_tensor(rb), torch.as_tensor(ri), torch.as_tensor(rh)].contiguous()
+    o, l = oracle.ssa_rows(qr, k, v, rb, rh, ri, Hq=Hq, n_sink=ns, window=win, scale=scale)
+    out = torch.as_tensor(o.reshape(B, S, Hq, dv)).float()
+    lse = torch.as_tensor(l.reshape(B, S, Hq)).permute(0, 2, 1).contiguous().float()
+    base = oracle.ssa_backward(q, k, v, dout, n_sink=ns, window=win, scale=scale)
+    same = oracle.ssa_backward(q, k, v, dout, n_sink=ns, window=win, scale=scale, out=out, lse=lse)
+    for x, y in zip(base, same):
+        np.testing.assert_allclose(x, y, atol=2e-6)      # out and lse went through fp32
+    shifted = oracle.ssa_backward(q, k, v, dout, n_sink=ns, window=win, scale=scale, out=out, lse=lse + 1.0)
+    np.testing.assert_allclose(shifted[2], same[2] * np.exp(-1.0), atol=2e-6)   # lse + 1 is rounded to fp32
+    # one row, out replaced by zeros: D = 0, so dQ_i = scale sum_j p_ij (dO_i . v_j) k_j
+    keep = torch.zeros(B, S, Hq, 1)
+    keep[0, 11, 1] = 1
+    zero_out = oracle.ssa_backward(q, k, v, dout * keep, n_sink=ns, window=win, scale=scale, out=out * 0, lse=lse)
+    live = sorted(_set_live(11, ns, win, None))
+    s = np.array([scale * float(q[0, 11, 1].double() @ k[0, j, 0].double()) for j in live])
+    pj = np.exp(s - float(lse[0, 1, 11]))
+    want = sum(scale * pj[n] * float(dout[0, 11, 1].double() @ v[0, j, 0].double()) * k[0, j, 0].double().numpy()
+               for n, j in enumerate(live))
+    np.testing.assert_allclose(zero_out[0][0, 11, 1], want, atol=1e-9)
+
+
 def test_backward_arguments_are_checked():
     q, k, v, dout = _rand((1, 4, 1, 4), 1), _rand((1, 4, 1, 4), 2), _rand((1, 4, 1, 4), 3), _rand((1, 4, 1, 4), 4)
     with pytest.raises(RuntimeError):
