@@ -53,6 +53,9 @@ def _load():
         lib.oracle_ssa_backward.restype = ci
         lib.oracle_ssa_backward.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, i64, ci, ci, i64, i64,
                                             i64, i64, i64, ctypes.c_double, vp, vp, vp, vp, vp, ci]
+        lib.oracle_ssa_backward_rows.restype = ci
+        lib.oracle_ssa_backward_rows.argtypes = [vp, vp, vp, vp, ci, i64, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64,
+                                                 i64, i64, i64, ctypes.c_double, vp, vp, vp, vp, vp, ci]
         _lib = lib
     return _lib
 
@@ -218,4 +221,48 @@ def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=
                                  int(n_threads or host_threads()))
     if rc != 0:
         raise RuntimeError(f"oracle_ssa_backward failed with code {rc}")
+    return dq, dk, dv
+
+
+def ssa_backward_rows(q_rows, k, v, dout_rows, row_b, row_h, row_i, *, Hq, n_sink, window, scale, block=None,
+                      n_threads=None, out_rows=None, lse_rows=None):
+    """:func:`ssa_backward` for a dO that is zero outside the listed rows (b, h, i).
+
+    q_rows [n, d_qk], dout_rows [n, d_v] (and, together, out_rows [n, d_v], lse_rows [n] float32).
+    Returns (dq_rows [n, d_qk], dk [B, S, Hkv, d_qk], dv [B, S, Hkv, d_v]) as float64.
+    """
+    lib = _load()
+    qa, ka, da = as_oracle_array(q_rows), as_oracle_array(k), as_oracle_array(dout_rows)
+    if isinstance(v, tuple) and v[0] == "alias":
+        va, d_v, v_stride = ka, int(v[1]), ka.shape[3]
+    else:
+        va = as_oracle_array(v)
+        d_v, v_stride = va.shape[3], va.shape[3]
+    if not (qa.dtype == ka.dtype == va.dtype == da.dtype):
+        raise TypeError("q_rows, k, v, dout_rows must share a dtype")
+    B, S, Hkv, k_stride = ka.shape
+    n, d_qk = qa.shape
+    rb = np.ascontiguousarray(row_b, dtype=np.int64)
+    rh = np.ascontiguousarray(row_h, dtype=np.int64)
+    ri = np.ascontiguousarray(row_i, dtype=np.int64)
+    assert rb.shape == rh.shape == ri.shape == (n,) and da.shape == (n, d_v)
+    oa = la = None
+    if (out_rows is None) != (lse_rows is None):
+        raise ValueError("out_rows and lse_rows come together")
+    if out_rows is not None:
+        oa, la = as_oracle_array(out_rows), as_oracle_array(lse_rows)
+        if oa.dtype != qa.dtype or oa.shape != (n, d_v) or la.dtype != np.float32 or la.shape != (n,):
+            raise TypeError("out_rows must be [n, d_v] in the dtype of q_rows, lse_rows [n] float32")
+    dq = np.empty((n, d_qk), dtype=np.float64)
+    dk = np.empty((B, S, Hkv, d_qk), dtype=np.float64)
+    dv = np.empty((B, S, Hkv, d_v), dtype=np.float64)
+    rc = lib.oracle_ssa_backward_rows(qa.ctypes.data, ka.ctypes.data, va.ctypes.data, da.ctypes.data, _dtype_code(qa), n,
+                                      rb.ctypes.data, rh.ctypes.data, ri.ctypes.data, B, int(Hq), Hkv, S, d_qk, d_v,
+                                      k_stride, v_stride, int(n_sink), min(int(window), INT64_MAX),
+                                      0 if block is None else int(block), float(scale),
+                                      oa.ctypes.data if oa is not None else None,
+                                      la.ctypes.data if la is not None else None,
+                                      dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, int(n_threads or host_threads()))
+    if rc != 0:
+        raise RuntimeError(f"oracle_ssa_backward_rows failed with code {rc}")
     return dq, dk, dv

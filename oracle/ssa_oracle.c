@@ -291,6 +291,7 @@ typedef struct {
     double scale;
     int64_t n_rows;
     const int64_t *rows;   /* flat (b * S + i) * Hq + h of the rows with a nonzero dO */
+    int compact;           /* q, dout, out_saved, lse_saved, dq hold the listed rows only, in list order */
     double *row_lse, *row_D;
     double *dq, *dk, *dv;
     int64_t next;          /* shared work counter */
@@ -309,7 +310,8 @@ static int bwd_row(bwd_t *J, int64_t r, double *score, double *o)
     const int64_t h = flat % J->Hq, bi = flat / J->Hq, i = bi % J->S, b = bi / J->S;
     const int64_t g = h / (J->Hq / J->Hkv);
     const int64_t S = J->S;
-    const int64_t qbase = flat * J->d_qk, dobase = flat * J->d_v;
+    const int64_t at = J->compact ? r : flat;   /* where this row sits in q, dout, out_saved, dq */
+    const int64_t qbase = at * J->d_qk, dobase = at * J->d_v;
     double m = -INFINITY;
     int64_t n_alive = 0;
     for (int64_t j = 0; j < S; ++j) {
@@ -326,7 +328,7 @@ static int bwd_row(bwd_t *J, int64_t r, double *score, double *o)
     for (int64_t j = 0; j < S; ++j)
         if (score[j] != -INFINITY) l += exp(score[j] - m);
     double lse = m + log(l);
-    if (J->lse_saved) lse = (double)J->lse_saved[(b * J->Hq + h) * S + i];
+    if (J->lse_saved) lse = (double)J->lse_saved[J->compact ? r : (b * J->Hq + h) * S + i];
     if (J->out_saved) {
         for (int c = 0; c < J->d_v; ++c) o[c] = widen(J->out_saved, J->dtype, dobase + c);
     } else {
@@ -383,7 +385,8 @@ static void bwd_key(bwd_t *J, int64_t key)
         const int64_t flat = J->rows[r];
         const int64_t h = flat % J->Hq, bi = flat / J->Hq, i = bi % J->S, rb = bi / J->S;
         if (rb != b || h / group != g || !bwd_alive(J, i, j)) continue;
-        const int64_t qbase = flat * J->d_qk, dobase = flat * J->d_v;
+        const int64_t at = J->compact ? r : flat;
+        const int64_t qbase = at * J->d_qk, dobase = at * J->d_v;
         double dot = 0.0, dP = 0.0;
         for (int c = 0; c < J->d_qk; ++c) dot += widen(J->q, J->dtype, qbase + c) * widen(J->k, J->dtype, kbase + c);
         for (int c = 0; c < J->d_v; ++c) dP += widen(J->dout, J->dtype, dobase + c) * widen(J->v, J->dtype, vbase + c);
@@ -458,6 +461,57 @@ int oracle_ssa_backward(const void *q, const void *k, const void *v, const void 
     J.n_sink = n_sink; J.window = window; J.block = block; J.scale = scale;
     J.n_rows = n_rows; J.rows = rows; J.dq = dq; J.dk = dk; J.dv = dv;
     J.out_saved = out_saved; J.lse_saved = lse_saved;
+    J.row_lse = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
+    J.row_D = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
+    if (!J.row_lse || !J.row_D) { free(rows); free(J.row_lse); free(J.row_D); return -3; }
+    if (n_threads < 1) n_threads = 1;
+    if (n_threads > 256) n_threads = 256;
+    bwd_run(&J, bwd_worker_rows, n_threads);
+    if (!J.failed) bwd_run(&J, bwd_worker_keys, n_threads);
+    free(rows); free(J.row_lse); free(J.row_D);
+    if (J.failed == 1) return -3;
+    if (J.failed == 2) return -2;
+    return 0;
+}
+
+/*
+ * The same for a list of query rows given on their own (every other row taken to have dO = 0):
+ *   q_rows [n, d_qk], dout_rows [n, d_v], row_b/h/i [n]; out_rows [n, d_v] and lse_rows [n] (fp32) as
+ *   out_saved / lse_saved above, or both NULL; dq_rows [n, d_qk] fp64; dk, dv dense as above.
+ * This is what lets a test at full sequence length check every dK and dV row: the device computes
+ * with a dense dO that is zero outside the listed rows.
+ */
+int oracle_ssa_backward_rows(const void *q_rows, const void *k, const void *v, const void *dout_rows, int dtype,
+                             int64_t n_rows, const int64_t *row_b, const int64_t *row_h, const int64_t *row_i,
+                             int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                             int64_t k_row_stride, int64_t v_row_stride,
+                             int64_t n_sink, int64_t window, int64_t block, double scale,
+                             const void *out_rows, const float *lse_rows,
+                             double *dq_rows, double *dk, double *dv, int n_threads)
+{
+    if (!q_rows || !k || !v || !dout_rows || !dq_rows || !dk || !dv || n_rows < 0) return -1;
+    if ((out_rows == NULL) != (lse_rows == NULL)) return -1;
+    if (dtype != ORACLE_DTYPE_F32 && dtype != ORACLE_DTYPE_BF16) return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || d_qk < 1 || d_v < 1) return -1;
+    if (k_row_stride < d_qk || v_row_stride < d_v || n_sink < 0 || window < 1 || block < 0) return -1;
+    int64_t *rows = (int64_t *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int64_t));
+    if (!rows) return -3;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        if (row_b[r] < 0 || row_b[r] >= B || row_h[r] < 0 || row_h[r] >= Hq || row_i[r] < 0 || row_i[r] >= S) {
+            free(rows);
+            return -1;
+        }
+        rows[r] = (row_b[r] * S + row_i[r]) * Hq + row_h[r];
+    }
+    memset(dk, 0, (size_t)B * S * Hkv * d_qk * sizeof(double));
+    memset(dv, 0, (size_t)B * S * Hkv * d_v * sizeof(double));
+    bwd_t J;
+    memset(&J, 0, sizeof J);
+    J.q = q_rows; J.k = k; J.v = v; J.dout = dout_rows; J.dtype = dtype; J.B = B; J.Hq = Hq; J.Hkv = Hkv; J.S = S;
+    J.d_qk = d_qk; J.d_v = d_v; J.k_row_stride = k_row_stride; J.v_row_stride = v_row_stride;
+    J.n_sink = n_sink; J.window = window; J.block = block; J.scale = scale;
+    J.n_rows = n_rows; J.rows = rows; J.compact = 1; J.dq = dq_rows; J.dk = dk; J.dv = dv;
+    J.out_saved = out_rows; J.lse_saved = lse_rows;
     J.row_lse = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
     J.row_D = (double *)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(double));
     if (!J.row_lse || !J.row_D) { free(rows); free(J.row_lse); free(J.row_D); return -3; }

@@ -95,3 +95,50 @@ def test_unsupported_group_size_is_refused(gpu_device):
     with pytest.raises(loza.LozaError) as e:
         H.run_backward(q, k, v, out, lse, dout, 4, 16, 0.1)
     assert "UNSUPPORTED" in str(e.value)
+
+
+def test_backward_at_the_128k_prefill_shape(gpu_device):
+    """S = 131072, 64 heads on one latent, sink 128 + window 8192: the launch the benchmark times.
+    The incoming gradient is zero outside a sample of rows, so the oracle can follow every one of
+    the 131072 dK rows (each is a sum over the sampled rows that see that key) and the sampled dQ
+    rows; every other dQ row must come out exactly zero. The device does the full work either way."""
+    cfg = W.CFG3
+    q, k, v = W.make_prefill_inputs(cfg, gpu_device)
+    assert v is k
+    rb, rh, ri = W.sample_rows(cfg, n_random=24, n_heads=3, edge=4)
+    n = len(rb)
+    idx = (torch.as_tensor(rb, device=gpu_device), torch.as_tensor(ri, device=gpu_device), torch.as_tensor(rh, device=gpu_device))
+    q_rows = q[idx].contiguous().cpu()
+    g = torch.Generator().manual_seed(77)
+    dout_rows = torch.randn((n, cfg.d_v), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    # what a forward pass would have stored for those rows, from the oracle's forward
+    o_rows, l_rows = oracle.ssa_rows(q_rows, k.cpu(), ("alias", cfg.d_v), rb, rh, ri, Hq=cfg.Hq, n_sink=cfg.n_sink,
+                                     window=cfg.window, scale=cfg.scale)
+    out_rows = torch.as_tensor(o_rows).to(torch.bfloat16)
+    lse_rows = torch.as_tensor(l_rows).to(torch.float32)
+    dout = torch.zeros(cfg.B, cfg.S, cfg.Hq, cfg.d_v, dtype=torch.bfloat16, device=gpu_device)
+    out = torch.zeros_like(dout)
+    lse = torch.full((cfg.B, cfg.Hq, cfg.S), 1.0e4, dtype=torch.float32, device=gpu_device)  # weights of the other rows: 0
+    dout[idx] = dout_rows.to(gpu_device)
+    out[idx] = out_rows.to(gpu_device)
+    lse[idx[0], idx[2], idx[1]] = lse_rows.to(gpu_device)
+    dq, dk, _ = H.run_backward(q, k, v, out, lse, dout, cfg.n_sink, cfg.window, cfg.scale)
+    rq, rk, rv = oracle.ssa_backward_rows(q_rows, k.cpu(), ("alias", cfg.d_v), dout_rows, rb, rh, ri, Hq=cfg.Hq,
+                                          n_sink=cfg.n_sink, window=cfg.window, scale=cfg.scale,
+                                          out_rows=out_rows, lse_rows=lse_rows)
+    rk[..., :cfg.d_v] += rv
+    got_q = dq[idx].double().cpu().numpy()
+    got_k = dk.double().cpu().numpy()
+    assert np.isfinite(got_q).all() and np.isfinite(got_k).all()
+    for name, gg, r in (("dq (sampled rows)", got_q, rq), ("dk (all keys)", got_k, rk)):
+        err = np.abs(gg - r)
+        over = float((err - H.grad_tolerance(r)).max())
+        print(f"[parity] cfg3 backward, {n} rows with a gradient: {name} max|err|={err.max():.3e} "
+              f"max|ref|={np.abs(r).max():.3e}", flush=True)
+        assert over <= 0.0, f"{name}: error exceeds its bound by {over}"
+    # rows without an incoming gradient: exactly zero, and all of them written
+    nonzero = (dq != 0).any(dim=-1)
+    want = torch.zeros_like(nonzero)
+    want[idx] = True
+    assert torch.equal(nonzero, want)
+    assert torch.isfinite(dq.float().sum())

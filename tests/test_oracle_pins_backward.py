@@ -188,6 +188,21 @@ def test_saved_forward_of_its_own_gives_the_gradient_and_the_substitution_is_the
     np.testing.assert_allclose(zero_out[0][0, 11, 1], want, atol=1e-9)
 
 
+def test_listed_rows_form_equals_the_dense_form_with_zeros_elsewhere():
+    B, S, Hq, d, dv, ns, win, block, scale = 2, 40, 4, 6, 5, 1, 2, 4, 0.5
+    q, k, v, dout = _rand((B, S, Hq, d), 71), _rand((B, S, 2, d), 72), _rand((B, S, 2, dv), 73), _rand((B, S, Hq, dv), 74)
+    rb = np.array([0, 1, 1, 0, 0]); rh = np.array([3, 0, 2, 1, 3]); ri = np.array([5, 39, 0, 17, 17])
+    keep = torch.zeros(B, S, Hq, 1)
+    keep[torch.as_tensor(rb), torch.as_tensor(ri), torch.as_tensor(rh)] = 1
+    dense = oracle.ssa_backward(q, k, v, dout * keep, n_sink=ns, window=win, scale=scale, block=block)
+    idx = (torch.as_tensor(rb), torch.as_tensor(ri), torch.as_tensor(rh))
+    dq_rows, dk, dvv = oracle.ssa_backward_rows(q[idx].contiguous(), k, v, dout[idx].contiguous(), rb, rh, ri, Hq=Hq,
+                                                 n_sink=ns, window=win, scale=scale, block=block)
+    np.testing.assert_allclose(dq_rows, dense[0][rb, ri, rh], atol=1e-14)
+    np.testing.assert_allclose(dk, dense[1], atol=1e-14)
+    np.testing.assert_allclose(dvv, dense[2], atol=1e-14)
+
+
 def test_backward_arguments_are_checked():
     q, k, v, dout = _rand((1, 4, 1, 4), 1), _rand((1, 4, 1, 4), 2), _rand((1, 4, 1, 4), 3), _rand((1, 4, 1, 4), 4)
     with pytest.raises(RuntimeError):
