@@ -110,10 +110,11 @@ struct BwdCfg {
     static constexpr int STAGE = NI * 1024;
     static constexpr int OFF_Y2 = N1 * 1024, OFF_STAT = (N1 + N2) * 1024;
     static constexpr int PROW = 32 * 2 + 16;          // LDS bytes per row of the dS / p buffers
-    static constexpr int XREGION = 2 * 32 * PROW;     // per block of X: dS rows, then p rows (also the T hand-over)
-    static_assert(XREGION >= 64 * 16 * 4, "the T hand-over must fit the region it shares");
+    static constexpr int XREGION = 2 * 32 * PROW;     // per block of X: dS rows, then p rows
+    static constexpr int XCH = 64 * 16 * 4;           // per block of X: the T block handed over, fp32
     static constexpr int OFF_BUF = 2 * STAGE;
-    static constexpr int LDS_BYTES = OFF_BUF + 2 * XREGION;
+    static constexpr int OFF_XCH = OFF_BUF + 2 * XREGION;
+    static constexpr int LDS_BYTES = OFF_XCH + 2 * XCH;
     static_assert(LDS_BYTES <= 160 * 1024, "does not fit the 160 KB LDS");
     // accumulator blocks (32 columns x 32 items of X) per wave
     static constexpr bool SPLIT_KV = KEYS && !ALIAS;  // half the waves take dK, the other half dV
@@ -293,6 +294,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
 
     char *region = smem + C::OFF_BUF + xb * C::XREGION;   // dS rows of this block of X, then its p rows
+    char *xch = smem + C::OFF_XCH + xb * C::XCH;          // T of this block of X, from its role-1 wave to its role-0 wave
     const int j_min_x = xt * 64, j_max_x = xt * 64 + 63;   // KEYS: the keys of this workgroup
 
     issue_tile(0, 0);
@@ -307,82 +309,89 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         f32x16 c;
 #pragma unroll
         for (int e = 0; e < 16; ++e) c[e] = 0.f;
-        if (role == 0) {
-            const char *ya = tile + ln * C::ROW1 + lh * 16;
+        // (fragments of the streamed tile are fetched PF steps ahead of the matrix instruction that
+        // uses them; the scheduling barriers keep the compiler from hoisting all of them to the top,
+        // which costs registers it then finds by spilling -- and a reload from scratch waits for every
+        // vector-memory operation in flight, the copy of the next tile included)
+        auto phase1 = [&](const char *ya, auto steps) {
+            constexpr int NS = decltype(steps)::value, PF = 4;
+            bf16x8 af[PF];
 #pragma unroll
-            for (int kk = 0; kk < DQK / 16; ++kk)
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ya + kk * 32), xf[kk], c, 0, 0, 0);
+            for (int d = 0; d < PF; ++d) af[d] = *(const bf16x8 *)(ya + d * 32);
+#pragma unroll
+            for (int kk = 0; kk < NS; ++kk) {
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % PF], xf[kk], c, 0, 0, 0);
+                if (kk + PF < NS) af[kk % PF] = *(const bf16x8 *)(ya + (kk + PF) * 32);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (role == 0) {
+            phase1(tile + ln * C::ROW1 + lh * 16, std::integral_constant<int, DQK / 16>{});
         } else {
             // T reads the second streamed tile when there is one (else the values are the key rows' prefix)
-            const char *ya = tile + (C::HAS_Y2 ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16;
-#pragma unroll
-            for (int kk = 0; kk < DV / 16; ++kk)
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ya + kk * 32), xf[kk], c, 0, 0, 0);
+            phase1(tile + (C::HAS_Y2 ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16, std::integral_constant<int, DV / 16>{});
         }
         if (role == 1) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 float4 w;
                 w.x = c[4 * qd]; w.y = c[4 * qd + 1]; w.z = c[4 * qd + 2]; w.w = c[4 * qd + 3];
-                *(float4 *)(region + (qd * 64 + lane) * 16) = w;
+                *(float4 *)(xch + (qd * 64 + lane) * 16) = w;
             }
         }
         __syncthreads();
 
         // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
+        // four values at a time: this lane's 16 values are four runs of four consecutive y, and a run
+        // is one 8-byte store into the [x][y] buffers (y contiguous)
         if (role == 0) {
-            float tt[16];
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const float4 w = *(const float4 *)(region + (qd * 64 + lane) * 16);
-                tt[4 * qd] = w.x; tt[4 * qd + 1] = w.y; tt[4 * qd + 2] = w.z; tt[4 * qd + 3] = w.w;
-            }
             const int y0 = y_tile(u) * 32;
-            float pv[16], dsv[16];
-            if (!KEYS) {
-                // lane = query row, elements = keys y0 + 8 (e >> 2) + 4 lh + (e & 3)
-                const bool interior = (y0 + 31 <= i_min) && ((y0 + 31 < n_sink) || (y0 >= w_lo_max));
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int j = y0 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                    const bool ok = interior || ((j <= x_i) & ((j < n_sink) | (j >= w_lo_row)));
-                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -x_lse2));
-                    pv[e] = ok ? pe : 0.f;
-                    dsv[e] = ok ? p.scale * pe * (tt[e] - x_D) : 0.f;
-                }
-            } else {
-                // lane = key, elements = query rows y0 + 8 (e >> 2) + 4 lh + (e & 3)
-                const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
-                const int i_lo = (int)((int64_t)y0 / G), i_hi = (int)(((int64_t)y0 + 31) / G);
-                const bool interior = ((int64_t)y0 + 31 < R) && (j_max_x < S) && (j_max_x <= i_lo) &&
-                                      ((j_max_x < n_sink) || (j_min_x >= window_begin_of(i_hi, window, block)));
-                const int j = (int)x_idx;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int y = 8 * (e >> 2) + 4 * lh + (e & 3);
-                    const float2 sd = stat[y];
-                    bool ok = true;
-                    if (!interior) {
-                        const int64_t r = (int64_t)y0 + y;
-                        const int i = (int)(r / G);
-                        ok = (r < R) & (j < S) & (j <= i) & ((j < n_sink) | (j >= window_begin_of(i, window, block)));
-                    }
-                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -sd.x));
-                    pv[e] = ok ? pe : 0.f;
-                    dsv[e] = ok ? p.scale * pe * (tt[e] - sd.y) : 0.f;
-                }
-            }
-            // [x][y] with y contiguous: this lane's 16 values are four runs of four consecutive y
             char *ps = region + ln * C::PROW + (4 * lh) * 2;
+            const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
+            bool interior;
+            if (!KEYS) {
+                // lane = query row, values = keys y0 + 8 qd + 4 lh + t
+                interior = (y0 + 31 <= i_min) && ((y0 + 31 < n_sink) || (y0 >= w_lo_max));
+            } else {
+                // lane = key, values = query rows y0 + 8 qd + 4 lh + t
+                const int i_lo = (int)((int64_t)y0 / G), i_hi = (int)(((int64_t)y0 + 31) / G);
+                interior = ((int64_t)y0 + 31 < R) && (j_max_x < S) && (j_max_x <= i_lo) &&
+                           ((j_max_x < n_sink) || (j_min_x >= window_begin_of(i_hi, window, block)));
+            }
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
+                const float4 t4 = *(const float4 *)(xch + (qd * 64 + lane) * 16);
+                const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
+                float pv[4], dsv[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int e = 4 * qd + t, y = 8 * qd + 4 * lh + t;
+                    float lse2, D;
+                    bool ok = true;
+                    if (!KEYS) {
+                        lse2 = x_lse2; D = x_D;
+                        const int j = y0 + y;
+                        if (!interior) ok = (j <= x_i) & ((j < n_sink) | (j >= w_lo_row));
+                    } else {
+                        const float2 sd = stat[y];
+                        lse2 = sd.x; D = sd.y;
+                        if (!interior) {
+                            const int64_t r = (int64_t)y0 + y;
+                            const int i = (int)(r / G), j = (int)x_idx;
+                            ok = (r < R) & (j < S) & (j <= i) & ((j < n_sink) | (j >= window_begin_of(i, window, block)));
+                        }
+                    }
+                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -lse2));
+                    pv[t] = ok ? pe : 0.f;
+                    dsv[t] = ok ? p.scale * pe * (tt[t] - D) : 0.f;
+                }
                 u32x2 w;
-                w[0] = pack_bf16(dsv[4 * qd], dsv[4 * qd + 1]);
-                w[1] = pack_bf16(dsv[4 * qd + 2], dsv[4 * qd + 3]);
+                w[0] = pack_bf16(dsv[0], dsv[1]);
+                w[1] = pack_bf16(dsv[2], dsv[3]);
                 *(u32x2 *)(ps + qd * 16) = w;
                 if (KEYS) {
-                    w[0] = pack_bf16(pv[4 * qd], pv[4 * qd + 1]);
-                    w[1] = pack_bf16(pv[4 * qd + 2], pv[4 * qd + 3]);
+                    w[0] = pack_bf16(pv[0], pv[1]);
+                    w[1] = pack_bf16(pv[2], pv[3]);
                     *(u32x2 *)(ps + 32 * C::PROW + qd * 16) = w;
                 }
             }
@@ -395,21 +404,32 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             const char *t1 = tile, *t2 = tile + C::OFF_Y2;
             auto phase2 = [&](auto half) {
                 constexpr int HF = decltype(half)::value;
+                constexpr int DB0 = C::SPLIT_KV ? 0 : HF * C::NACC;
+                // the matrix instructions of this wave as a flat list: (key step, accumulator, product);
+                // product 1 (Y2^T p) exists for dV only
+                auto has2 = [](int a) { return KEYS && !C::SPLIT_KV && DB0 + a < DV / 32; };
+                auto frag = [&](int ks, int a, int prod) {
+                    if (C::SPLIT_KV) return HF == 0 ? read_transposed(t1, C::ROW1, a, ks, lane) : read_transposed(t2, C::ROW2, a, ks, lane);
+                    return prod == 0 ? read_transposed(t1, C::ROW1, DB0 + a, ks, lane) : read_transposed(t2, C::ROW2, DB0 + a, ks, lane);
+                };
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const bf16x8 b_ds = *(const bf16x8 *)(bs + ks * 32);
                     bf16x8 b_p = b_ds;
                     if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW + ks * 32);
+                    bf16x8 nxt = frag(ks, 0, 0);
 #pragma unroll
                     for (int a = 0; a < C::NACC; ++a) {
-                        if (C::SPLIT_KV) {
-                            if (HF == 0) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t1, C::ROW1, a, ks, lane), b_ds, acc[a], 0, 0, 0);
-                            else acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t2, C::ROW2, a, ks, lane), b_p, acc[a], 0, 0, 0);
-                        } else {
-                            constexpr int DB0 = HF * C::NACC;
-                            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t1, C::ROW1, DB0 + a, ks, lane), b_ds, acc[a], 0, 0, 0);
-                            if (KEYS && DB0 + a < DV / 32)
-                                acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_transposed(t2, C::ROW2, DB0 + a, ks, lane), b_p, acc[a], 0, 0, 0);
+                        const bf16x8 cur = nxt;
+                        if (has2(a)) nxt = frag(ks, a, 1);
+                        else if (a + 1 < C::NACC) nxt = frag(ks, a + 1, 0);
+                        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, (C::SPLIT_KV && HF == 1) ? b_p : b_ds, acc[a], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (has2(a)) {
+                            const bf16x8 cur2 = nxt;
+                            if (a + 1 < C::NACC) nxt = frag(ks, a + 1, 0);
+                            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur2, b_p, acc[a], 0, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                 }

@@ -264,6 +264,34 @@ def test_decode_split_count_and_workspace_size():
     assert B.loza_ssa_decode_num_splits(3, 32, 5, 10000, 16, 512) == 0
 
 
+def test_backward_rejects_bad_arguments_and_sizes_its_workspace():
+    big = 1 << 40
+
+    def call(q=FAKE, v=FAKE, dv=None, dout=FAKE, Hq=64, Hkv=1, S=4096, d_qk=576, d_v=512, n_sink=128, window=512,
+             scale=0.07, ws=FAKE, ws_bytes=big):
+        return B.lib().loza_ssa_backward(q, FAKE, v, FAKE, FAKE, dout, FAKE, FAKE, dv, 1, Hq, Hkv, S, d_qk, d_v,
+                                         n_sink, window, scale, ws, ws_bytes, None)
+    assert call(q=None) == ERR_NULL and call(dout=None) == ERR_NULL
+    assert call(v=FAKE + 64, d_qk=128, d_v=128, dv=None) == ERR_NULL        # separate values need their own dv
+    assert call(window=0) == ERR_SHAPE and call(n_sink=-1) == ERR_SHAPE and call(scale=0.0) == ERR_SHAPE
+    assert call(d_qk=96, d_v=96) == ERR_UNSUPPORTED
+    assert call(Hq=3) == ERR_UNSUPPORTED and call(Hq=48) == ERR_UNSUPPORTED  # heads per group: 2^n <= 32 or 32 n
+    assert call(Hq=96) != ERR_UNSUPPORTED
+    assert call(ws=None) == ERR_WORKSPACE and call(ws_bytes=16) == ERR_WORKSPACE
+    assert call(dout=FAKE + 8) == ERR_ALIGN
+    assert B.lib().loza_ssa_backward_blocks(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, 1, 4096, 576, 512,
+                                            1, 7, 0, 0.07, FAKE, big, None) == ERR_SHAPE
+    # the row statistics (8 bytes per query row, rows padded to 32 per kv head) ...
+    assert B.loza_ssa_backward_workspace_bytes(2, 8, 2, 1000, 128, 128, 0, 100, False) == 2 * 2 * 4000 * 8
+    # ... plus, with sink keys, fp32 partial sums of the sink key tiles: one per chunk of query rows
+    n = B.loza_ssa_backward_workspace_bytes(1, 64, 1, 131072, 576, 512, 128, 8192, True)
+    stat = 131072 * 64 * 8
+    assert n > stat and (n - stat) % (2 * 64 * 576 * 4) == 0       # two key tiles of 64 keys, 576 columns
+    assert B.loza_ssa_backward_workspace_bytes(1, 3, 1, 1000, 128, 128, 0, 100, False) == 0
+    assert B.loza_ssa_backward_workspace_bytes_blocks(1, 64, 1, 4096, 576, 512, 1, 7, 0, True) == 0
+    assert B.loza_ssa_backward_workspace_bytes_blocks(1, 64, 1, 4096, 576, 512, 1, 7, 128, True) > 0
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
