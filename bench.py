@@ -34,6 +34,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward of the timed prefill")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the untimed-region extras: the 32K MHA and the 1M-token MLA prefill configurations")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -195,6 +196,32 @@ def main() -> int:
             "decode_gbps": round(blk_rows * dc.d_qk * 2 / (blk_decode_ms * 1e-3) / 1e9, 1),
             "decode_speedup_vs_full": round(full_decode_ms / blk_decode_ms, 1),
         }
+
+    # ---- backward of the same prefill (outside the timed step): dq and the gradient of the latent ---------
+    if not args.no_backward:
+        gen = torch.Generator(device=dev).manual_seed(7)
+        d_out = torch.randn(out.shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        d_q, d_k = torch.empty_like(q), torch.empty_like(k)
+        d_v = None if v is k else torch.empty_like(v)
+        ws_bwd = torch.empty(loza.loza_ssa_backward_workspace_bytes(pc.B, pc.Hq, pc.Hkv, pc.S, pc.d_qk, pc.d_v, pc.n_sink,
+                                                                    pc.window, v is k), dtype=torch.uint8, device=dev)
+        prefill(pc.window)  # out, lse of the sparse pattern again (the comparators above overwrote them)
+
+        def backward():
+            loza.loza_ssa_backward(q, k, v, out, lse, d_out, d_q, d_k, d_v, pc.n_sink, pc.window, pc.scale, ws_bwd)
+        backward(); torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record(); backward(); eb.record(); torch.cuda.synchronize()
+        bwd_ms = ea.elapsed_time(eb)
+        # five contractions per live pair: S and dQ and dK over d_qk, dP and dV over d_v
+        bwd_flop = 2.0 * loza.loza_ssa_live_pairs(pc.S, pc.n_sink, pc.window) * (3 * pc.d_qk + 2 * pc.d_v) * pc.Hq * pc.B
+        result["backward"] = {
+            "workload": "gradients of the timed prefill (dq, and dk + dv as the gradient of the shared latent)",
+            "ms": round(bwd_ms, 2), "tflops": round(bwd_flop / (bwd_ms * 1e-3) / 1e12, 1),
+            "mfma_frac": round(bwd_flop / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "times_forward": round(bwd_ms / prefill_ms, 2),
+        }
+        del d_out, d_q, d_k, ws_bwd
 
     # ---- CPU oracle on a bounded sample of the same prefill workload ----------------------------------
     if not args.no_cpu_baseline:

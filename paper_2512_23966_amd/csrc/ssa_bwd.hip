@@ -119,7 +119,11 @@ struct BwdCfg {
     // accumulator blocks (32 columns x 32 items of X) per wave
     static constexpr bool SPLIT_KV = KEYS && !ALIAS;  // half the waves take dK, the other half dV
     static_assert(!SPLIT_KV || DQK == DV, "separate values: equal widths only");
-    static constexpr int NACC = SPLIT_KV ? DQK / 32 : DQK / 64;
+    // Column blocks of the waves of role 0 and of role 1. Where role 0 carries the most (wide keys,
+    // KEYS: the longer phase 1, the elementwise step, two products per block) it takes one block
+    // fewer: its registers then hold its 36 operand fragments beside its accumulators.
+    static constexpr int NACC0 = SPLIT_KV ? DQK / 32 : DQK / 64 - ((KEYS && DQK == 576) ? 1 : 0);
+    static constexpr int NACC1 = SPLIT_KV ? DQK / 32 : DQK / 32 - NACC0;
     static_assert(DQK % 64 == 0 && DV % 32 == 0 && DV <= DQK, "head widths");
 };
 
@@ -195,9 +199,14 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     }
     auto y_tile = [&](int t) { return KEYS ? yt_begin + t : (t < nA ? t : wt0 + (t - nA)); };
 
+    // From here on the two roles run separate instantiations of the same code (role 0: S = Y1 X1^T and
+    // the elementwise step; role 1: T = Y2 X2^T): each then has registers for its own operand fragments
+    // and its own share of the accumulators, and no branch on the role sits inside the tile loop. The
+    // workgroup barriers of the two instantiations pair up one to one.
+    auto run = [&](auto role_c) {
+    constexpr int ROLE = decltype(role_c)::value;
     // ---- the stationary side: matrix-core B operands in registers --------------------------------
-    constexpr int NKK = DQK / 16;
-    bf16x8 xf[NKK];
+    bf16x8 xf[ROLE == 0 ? DQK / 16 : DV / 16];
     const int64_t x_idx = (int64_t)xt * 64 + xb * 32 + ln;          // row (i * G + head) or key
     const int64_t x_c = x_idx < (KEYS ? S : R) ? x_idx : (KEYS ? S : R) - 1;
     int x_i = 0;                                                     // !KEYS: position of this lane's row
@@ -209,26 +218,21 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             const int hh = (int)(x_c - i * G);
             x_i = (int)i;
             const int64_t qrow = (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh);
-            xp = role == 0 ? p.q + qrow * DQK : p.dout + qrow * DV;
+            xp = ROLE == 0 ? p.q + qrow * DQK : p.dout + qrow * DV;
             const float2 st = p.rowstat[((int64_t)b * p.Hkv + g) * p.r_pad + x_c];
             x_lse2 = st.x;
             x_D = st.y;
         } else {
             const int64_t krow = ((int64_t)b * S + x_c) * p.Hkv + g;
-            xp = role == 0 ? p.k + krow * DQK : p.v + krow * (ALIAS ? DQK : DV);
+            xp = ROLE == 0 ? p.k + krow * DQK : p.v + krow * (ALIAS ? DQK : DV);
         }
         xp += lh * 8;
-        // (two loops with constant bounds: a bound that depends on the role would turn every
-        // matrix instruction below into a predicated one)
-        if (role == 0) {
 #pragma unroll
-            for (int kk = 0; kk < DQK / 16; ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < DV / 16; ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
-        }
+        for (int kk = 0; kk < (ROLE == 0 ? DQK / 16 : DV / 16); ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
     }
     const int w_lo_row = KEYS ? 0 : window_begin_of(x_i, window, block);
+    int g_shift = 5;  // KEYS: log2(G) for G < 32, else 5
+    if (G < 32) { g_shift = 0; while ((1 << g_shift) < G) ++g_shift; }
 
     // ---- global -> LDS copy plan of a streamed tile (the same for every tile) ---------------------
     // Instruction n fills LDS bytes [n*1024, n*1024 + 1024) of the stage: slot n*64 + lane of the
@@ -260,7 +264,12 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     }
     const char *y1_all = KEYS ? (const char *)p.q : (const char *)p.k;
     const char *y2_all = KEYS ? (const char *)p.dout : (const char *)p.v;
-    auto issue_tile = [&](int t, int stage) {
+    // what the copy instructions of one tile share (all wave-uniform)
+    struct TileCopy {
+        const char *b1, *b2, *b3;
+        uint32_t max1, max2, dst;
+    };
+    auto plan_tile = [&](int t, int stage) {
         const int64_t y0 = (int64_t)y_tile(t) * 32;                  // first row / key of the tile
         const int64_t y_left = (KEYS ? R : S) - 1 - y0;
         const int lim = y_left < 31 ? (int)y_left : 31;              // last valid item of the tile
@@ -272,24 +281,27 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         } else {
             row0 = ((int64_t)b * S + y0) * p.Hkv + g;
         }
-        const char *b1 = y1_all + row0 * DQK * 2;
-        const char *b2 = y2_all + row0 * W2 * 2;
-        const char *b3 = (const char *)(p.rowstat + ((int64_t)b * p.Hkv + g) * p.r_pad + y0);
-        const uint32_t max1 = item_offset(lim, DQK) + (C::CPR1 - 2) * 16;
-        const uint32_t max2 = item_offset(lim, W2) + (C::CPR2 - 2) * 16;
-        const uint32_t dst = smem_lds + stage * C::STAGE;
-#pragma unroll
-        for (int u = 0; u < C::PER_WAVE; ++u) {
-            const int n = u * 4 + wave;  // wave-uniform
-            if (n < C::N1) copy_1k(b1, yoff[u] < max1 ? yoff[u] : max1, dst + n * 1024);
-            else if (n < C::N1 + C::N2) copy_1k(b2, yoff[u] < max2 ? yoff[u] : max2, dst + n * 1024);
-            else if (n < C::NI) copy_1k(b3, yoff[u], dst + n * 1024);
-        }
+        TileCopy tc;
+        tc.b1 = y1_all + row0 * DQK * 2;
+        tc.b2 = y2_all + row0 * W2 * 2;
+        tc.b3 = (const char *)(p.rowstat + ((int64_t)b * p.Hkv + g) * p.r_pad + y0);
+        tc.max1 = item_offset(lim, DQK) + (C::CPR1 - 2) * 16;
+        tc.max2 = item_offset(lim, W2) + (C::CPR2 - 2) * 16;
+        tc.dst = smem_lds + stage * C::STAGE;
+        return tc;
+    };
+    // copy instruction u of this wave (u < PER_WAVE, a constant after unrolling)
+    auto issue_one = [&](const TileCopy &tc, int u) {
+        const int n = u * 4 + wave;  // wave-uniform
+        if (n < C::N1) copy_1k(tc.b1, yoff[u] < tc.max1 ? yoff[u] : tc.max1, tc.dst + n * 1024);
+        else if (n < C::N1 + C::N2) copy_1k(tc.b2, yoff[u] < tc.max2 ? yoff[u] : tc.max2, tc.dst + n * 1024);
+        else if (n < C::NI) copy_1k(tc.b3, yoff[u], tc.dst + n * 1024);
     };
 
-    f32x16 acc[C::NACC];
+    constexpr int NA = ROLE == 0 ? C::NACC0 : C::NACC1;  // accumulator blocks of this wave
+    f32x16 acc[NA];
 #pragma unroll
-    for (int a = 0; a < C::NACC; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
 
@@ -297,12 +309,25 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     char *xch = smem + C::OFF_XCH + xb * C::XCH;          // T of this block of X, from its role-1 wave to its role-0 wave
     const int j_min_x = xt * 64, j_max_x = xt * 64 + 63;   // KEYS: the keys of this workgroup
 
-    issue_tile(0, 0);
+    {
+        const TileCopy tc0 = plan_tile(0, 0);
+#pragma unroll
+        for (int cu = 0; cu < C::PER_WAVE; ++cu) issue_one(tc0, cu);
+    }
+    // Everything requested from global memory so far (operand fragments, row statistics) is waited
+    // for here, with a wait the compiler sees: left to its own bookkeeping it would wait for those
+    // loads inside the loop, with counts that also drain the tile copies it does not know about.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    // The copy instructions of the next tile are issued a few at a time between the matrix
+    // instructions of both phases: issued in one burst they fill the memory pipeline's queue and the
+    // wave stalls on them for longer than a phase takes (measured).
+    constexpr int COPIES1 = (C::PER_WAVE + 1) / 2, COPIES2 = C::PER_WAVE - COPIES1;
     for (int u = 0; u < nt; ++u) {
         const int st = u & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
         __syncthreads();                                  // ... everyone's; tile u - 1 is no longer read
-        if (u + 1 < nt) issue_tile(u + 1, st ^ 1);
+        const bool more = u + 1 < nt;
+        const TileCopy tc = plan_tile(more ? u + 1 : u, st ^ 1);
         const char *tile = smem + st * C::STAGE;
 
         // ---- phase 1: one 32 x 32 block of S or T ---------------------------------------------------
@@ -313,8 +338,11 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // uses them; the scheduling barriers keep the compiler from hoisting all of them to the top,
         // which costs registers it then finds by spilling -- and a reload from scratch waits for every
         // vector-memory operation in flight, the copy of the next tile included)
-        auto phase1 = [&](const char *ya, auto steps) {
-            constexpr int NS = decltype(steps)::value, PF = 4;
+        {
+            constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 4, EVERY = NS / COPIES1;
+            // S reads the first streamed tile; T the second when there is one (else the values are the
+            // key rows' prefix)
+            const char *ya = tile + ((ROLE == 1 && C::HAS_Y2) ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16;
             bf16x8 af[PF];
 #pragma unroll
             for (int d = 0; d < PF; ++d) af[d] = *(const bf16x8 *)(ya + d * 32);
@@ -322,16 +350,11 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             for (int kk = 0; kk < NS; ++kk) {
                 c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % PF], xf[kk], c, 0, 0, 0);
                 if (kk + PF < NS) af[kk % PF] = *(const bf16x8 *)(ya + (kk + PF) * 32);
+                if (kk % EVERY == 0 && kk / EVERY < COPIES1 && more) issue_one(tc, kk / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        };
-        if (role == 0) {
-            phase1(tile + ln * C::ROW1 + lh * 16, std::integral_constant<int, DQK / 16>{});
-        } else {
-            // T reads the second streamed tile when there is one (else the values are the key rows' prefix)
-            phase1(tile + (C::HAS_Y2 ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16, std::integral_constant<int, DV / 16>{});
         }
-        if (role == 1) {
+        if constexpr (ROLE == 1) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 float4 w;
@@ -344,7 +367,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
         // four values at a time: this lane's 16 values are four runs of four consecutive y, and a run
         // is one 8-byte store into the [x][y] buffers (y contiguous)
-        if (role == 0) {
+        if constexpr (ROLE == 0) {
             const int y0 = y_tile(u) * 32;
             char *ps = region + ln * C::PROW + (4 * lh) * 2;
             const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
@@ -353,11 +376,15 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 // lane = query row, values = keys y0 + 8 qd + 4 lh + t
                 interior = (y0 + 31 <= i_min) && ((y0 + 31 < n_sink) || (y0 >= w_lo_max));
             } else {
-                // lane = key, values = query rows y0 + 8 qd + 4 lh + t
-                const int i_lo = (int)((int64_t)y0 / G), i_hi = (int)(((int64_t)y0 + 31) / G);
+                // lane = key, values = query rows y0 + 8 qd + 4 lh + t (row counts fit 32 bits)
+                const int i_lo = y0 / G, i_hi = (y0 + 31) / G;
                 interior = ((int64_t)y0 + 31 < R) && (j_max_x < S) && (j_max_x <= i_lo) &&
                            ((j_max_x < n_sink) || (j_min_x >= window_begin_of(i_hi, window, block)));
             }
+            // KEYS: position of row y0 + y is i_tile + (y >> g_shift): a tile is 32 / G whole positions
+            // (G a power of two) or part of one position (G a multiple of 32: the shift drops every y)
+            const int i_tile = KEYS ? y0 / G : 0;
+            const int w_lo_tile = KEYS ? window_begin_of(i_tile, window, block) : 0;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const float4 t4 = *(const float4 *)(xch + (qd * 64 + lane) * 16);
@@ -376,9 +403,9 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                         const float2 sd = stat[y];
                         lse2 = sd.x; D = sd.y;
                         if (!interior) {
-                            const int64_t r = (int64_t)y0 + y;
-                            const int i = (int)(r / G), j = (int)x_idx;
-                            ok = (r < R) & (j < S) & (j <= i) & ((j < n_sink) | (j >= window_begin_of(i, window, block)));
+                            const int i = i_tile + (y >> g_shift), j = (int)x_idx;
+                            const int w_lo = G >= 32 ? w_lo_tile : window_begin_of(i, window, block);
+                            ok = (y0 + y < (int)R) & (j < (int)S) & (j <= i) & ((j < n_sink) | (j >= w_lo));
                         }
                     }
                     const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -lse2));
@@ -402,52 +429,58 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         {
             const char *bs = region + ln * C::PROW + lh * 16;
             const char *t1 = tile, *t2 = tile + C::OFF_Y2;
-            auto phase2 = [&](auto half) {
-                constexpr int HF = decltype(half)::value;
-                constexpr int DB0 = C::SPLIT_KV ? 0 : HF * C::NACC;
-                // the matrix instructions of this wave as a flat list: (key step, accumulator, product);
-                // product 1 (Y2^T p) exists for dV only
-                auto has2 = [](int a) { return KEYS && !C::SPLIT_KV && DB0 + a < DV / 32; };
-                auto frag = [&](int ks, int a, int prod) {
+            {
+                constexpr int HF = ROLE;
+                constexpr int DB0 = (C::SPLIT_KV || HF == 0) ? 0 : C::NACC0;
+                // The matrix instructions of this wave as a flat list of (key step, accumulator, product);
+                // product 1 (Y2^T p, the dV part of a shared accumulator) exists for the first d_v columns
+                // only. Operand fragments are fetched PF entries ahead.
+                constexpr int N2 = (KEYS && !C::SPLIT_KV) ? ((DV / 32 - DB0) < 0 ? 0 : ((DV / 32 - DB0) < NA ? (DV / 32 - DB0) : NA)) : 0;
+                constexpr int PER_KS = NA + N2;            // accumulators a < N2 take two products
+                constexpr int NM = 2 * PER_KS, PF = 3, EVERY = COPIES2 > 0 ? NM / COPIES2 : NM;
+                auto entry = [](int m, int &ks, int &a, int &prod) {
+                    ks = m / PER_KS;
+                    const int r = m % PER_KS;
+                    if (r < 2 * N2) { a = r / 2; prod = r % 2; } else { a = r - N2; prod = 0; }
+                };
+                auto frag = [&](int m) {
+                    int ks, a, prod;
+                    entry(m, ks, a, prod);
                     if (C::SPLIT_KV) return HF == 0 ? read_transposed(t1, C::ROW1, a, ks, lane) : read_transposed(t2, C::ROW2, a, ks, lane);
                     return prod == 0 ? read_transposed(t1, C::ROW1, DB0 + a, ks, lane) : read_transposed(t2, C::ROW2, DB0 + a, ks, lane);
                 };
+                bf16x8 b_ds = *(const bf16x8 *)bs, b_p = b_ds;
+                if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW);
+                bf16x8 fr[PF];
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const bf16x8 b_ds = *(const bf16x8 *)(bs + ks * 32);
-                    bf16x8 b_p = b_ds;
-                    if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW + ks * 32);
-                    bf16x8 nxt = frag(ks, 0, 0);
+                for (int m = 0; m < PF && m < NM; ++m) fr[m] = frag(m);
 #pragma unroll
-                    for (int a = 0; a < C::NACC; ++a) {
-                        const bf16x8 cur = nxt;
-                        if (has2(a)) nxt = frag(ks, a, 1);
-                        else if (a + 1 < C::NACC) nxt = frag(ks, a + 1, 0);
-                        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, (C::SPLIT_KV && HF == 1) ? b_p : b_ds, acc[a], 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (has2(a)) {
-                            const bf16x8 cur2 = nxt;
-                            if (a + 1 < C::NACC) nxt = frag(ks, a + 1, 0);
-                            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur2, b_p, acc[a], 0, 0, 0);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                for (int m = 0; m < NM; ++m) {
+                    int ks, a, prod;
+                    entry(m, ks, a, prod);
+                    const bool use_p = C::SPLIT_KV ? HF == 1 : prod == 1;
+                    acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % PF], use_p ? b_p : b_ds, acc[a], 0, 0, 0);
+                    if (m + PF < NM) fr[m % PF] = frag(m + PF);
+                    if (m == PER_KS - 1) {  // the second key step's dS and p
+                        b_ds = *(const bf16x8 *)(bs + 32);
+                        if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW + 32);
                     }
+                    if (m % EVERY == 0 && m / EVERY < COPIES2 && more) issue_one(tc, COPIES1 + m / EVERY);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            };
-            if (role == 0) phase2(std::integral_constant<int, 0>{});
-            else phase2(std::integral_constant<int, 1>{});
+            }
         }
     }
 
     // ---- epilogue: lane = item of X, 16 values of a block = four runs of four consecutive columns ------
     if (x_idx >= (KEYS ? S : R)) return;
-    const int hf = role;
+    constexpr int hf = ROLE;
     if (!KEYS) {
         const int64_t i = x_idx / G;
         const int hh = (int)(x_idx - i * G);
-        uint16_t *op = p.dq + (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh) * DQK + hf * C::NACC * 32 + 4 * lh;
+        uint16_t *op = p.dq + (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh) * DQK + hf * C::NACC0 * 32 + 4 * lh;
 #pragma unroll
-        for (int a = 0; a < C::NACC; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 u32x2 w;
@@ -457,16 +490,16 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             }
     } else {
         // column of the first accumulator block of this wave in the row [dK (d_qk) | dV (d_v, separate values only)]
-        const int col0 = C::SPLIT_KV ? hf * DQK : hf * C::NACC * 32;
+        const int col0 = C::SPLIT_KV ? hf * DQK : hf * C::NACC0 * 32;
         if (partial) {
             constexpr int COLS = C::SPLIT_KV ? DQK + DV : DQK;
             float *op = p.part + ((((int64_t)b * p.Hkv + g) * p.n_sink_kt + xt) * p.max_chunks + chunk) * 64 * COLS +
                         (int64_t)(xb * 32 + ln) * COLS + col0 + 4 * lh;
 #pragma unroll
-            for (int a = 0; a < C::NACC; ++a)
+            for (int a = 0; a < NA; ++a)
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
-                    float4 w;
+                        float4 w;
                     w.x = acc[a][4 * qd]; w.y = acc[a][4 * qd + 1]; w.z = acc[a][4 * qd + 2]; w.w = acc[a][4 * qd + 3];
                     *(float4 *)(op + a * 32 + qd * 8) = w;
                 }
@@ -474,16 +507,19 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             const int64_t krow = ((int64_t)b * S + x_idx) * p.Hkv + g;
             uint16_t *op = (C::SPLIT_KV && hf == 1) ? p.dv + krow * DV + 4 * lh : p.dk + krow * DQK + col0 + 4 * lh;
 #pragma unroll
-            for (int a = 0; a < C::NACC; ++a)
+            for (int a = 0; a < NA; ++a)
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
-                    u32x2 w;
+                        u32x2 w;
                     w[0] = pack_bf16(acc[a][4 * qd], acc[a][4 * qd + 1]);
                     w[1] = pack_bf16(acc[a][4 * qd + 2], acc[a][4 * qd + 3]);
                     *(u32x2 *)(op + a * 32 + qd * 8) = w;
                 }
         }
     }
+    };
+    if (role == 0) run(std::integral_constant<int, 0>{});
+    else run(std::integral_constant<int, 1>{});
 }
 
 // Sum of the chunk partials of the key tiles that hold sink keys, in chunk order, rounded once.
