@@ -385,6 +385,9 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             // (G a power of two) or part of one position (G a multiple of 32: the shift drops every y)
             const int i_tile = KEYS ? y0 / G : 0;
             const int w_lo_tile = KEYS ? window_begin_of(i_tile, window, block) : 0;
+            // (one branch for the whole tile: interior tiles, nearly all of them, evaluate no predicate)
+            auto elementwise = [&](auto masked) {
+            constexpr bool MASKED = decltype(masked)::value;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 const float4 t4 = *(const float4 *)(xch + (qd * 64 + lane) * 16);
@@ -398,11 +401,11 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                     if (!KEYS) {
                         lse2 = x_lse2; D = x_D;
                         const int j = y0 + y;
-                        if (!interior) ok = (j <= x_i) & ((j < n_sink) | (j >= w_lo_row));
+                        if (MASKED) ok = (j <= x_i) & ((j < n_sink) | (j >= w_lo_row));
                     } else {
                         const float2 sd = stat[y];
                         lse2 = sd.x; D = sd.y;
-                        if (!interior) {
+                        if (MASKED) {
                             const int i = i_tile + (y >> g_shift), j = (int)x_idx;
                             const int w_lo = G >= 32 ? w_lo_tile : window_begin_of(i, window, block);
                             ok = (y0 + y < (int)R) & (j < (int)S) & (j <= i) & ((j < n_sink) | (j >= w_lo));
@@ -422,6 +425,9 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                     *(u32x2 *)(ps + 32 * C::PROW + qd * 16) = w;
                 }
             }
+            };
+            if (interior) elementwise(std::false_type{});
+            else elementwise(std::true_type{});
         }
         __syncthreads();
 
