@@ -141,6 +141,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     const int n_sink = p.n_sink, window = p.window, block = p.block;
 
     // ---- which work item ----------------------------------------------------------------------------
+    const int n_kt = (int)((S + 63) / 64);  // key tiles of 64 keys
     int b, g, xt, chunk = 0;
     bool partial = false;  // KEYS: leave an fp32 partial sum for the reduce kernel
     if (!KEYS) {
@@ -151,9 +152,15 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         g = id % p.Hkv;
         b = id / p.Hkv;
     } else {
-        const int n_kt = (int)((S + 63) / 64);
         const int items = p.n_sink_kt * p.max_chunks + (n_kt - p.n_sink_kt);
+        // Workgroups go to the eight XCDs round-robin and every XCD has an L2 of its own. Handing every
+        // XCD one contiguous eighth of the items makes the workgroups that share an L2 neighbouring key
+        // tiles, whose row ranges overlap almost completely (see the rotation below).
         int id = blockIdx.x;
+        {
+            const int total = gridDim.x, eighth = total / 8;
+            if (id < eighth * 8) id = (id % 8) * eighth + id / 8;
+        }
         const int it = id % items;
         id /= items;
         g = id % p.Hkv;
@@ -170,7 +177,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     // ---- streamed tiles of this item -------------------------------------------------------------
     // !KEYS: the live key tiles of rows [xt*64, xt*64+64): sink tiles [0, nA), then window tiles.
     // KEYS: the row tiles [yt_begin, yt_begin + nt) that can see keys [xt*64, xt*64+64).
-    int nt, nA = 0, wt0 = 0, yt_begin = 0;
+    int nt, nA = 0, wt0 = 0, yt_begin = 0, yt_start = 0;
     int i_min = 0, i_max = 0, w_lo_max = 0;
     if (!KEYS) {
         const int64_t r_last = (int64_t)xt * 64 + 63 < R ? (int64_t)xt * 64 + 63 : R - 1;
@@ -196,8 +203,27 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         }
         nt = yt_end - yt_begin;
         if (nt <= 0) return;  // a chunk beyond the rows of this key tile (the reduce kernel knows)
+        // Neighbouring key tiles see almost the same rows, each range shifted by 64 positions. Left to
+        // start at its own first row tile, every workgroup would stream its q and dout rows at a
+        // different place at any moment, and all of it would come from HBM (at the 128K shape: 2.4 TB
+        // per launch). Instead the 32 key tiles of a group (the workgroups that run together on one
+        // XCD) all start at the first row tile of the group's last member and wrap around inside their
+        // own range: they then ask for the same row tile at about the same time, and one fetch into
+        // the shared L2 serves all of them.
+        yt_start = yt_begin;
+        if (xt >= p.n_sink_kt) {
+            const int last = p.n_sink_kt + ((xt - p.n_sink_kt) / 32) * 32 + 31;
+            int a_lo, a_hi;
+            bwd_key_tile_rows(p, last < n_kt - 1 ? last : n_kt - 1, a_lo, a_hi);
+            if (a_lo >= yt_begin && a_lo < yt_end) yt_start = a_lo;
+        }
     }
-    auto y_tile = [&](int t) { return KEYS ? yt_begin + t : (t < nA ? t : wt0 + (t - nA)); };
+    const int yt_wrap = yt_begin + nt;
+    auto y_tile = [&](int t) {
+        if (!KEYS) return t < nA ? t : wt0 + (t - nA);
+        const int yt = yt_start + t;
+        return yt < yt_wrap ? yt : yt - nt;
+    };
 
     // From here on the two roles run separate instantiations of the same code (role 0: S = Y1 X1^T and
     // the elementwise step; role 1: T = Y2 X2^T): each then has registers for its own operand fragments
