@@ -33,6 +33,10 @@ def _case(device, B, S, Hq, Hkv, d_qk, d_v, alias, seed=0):
     (1, 130, 64, 1, 2, 32),         # block-granular
     (1, 150, 64, 7, None, None),    # window = infinity: causal attention
     (1, 33, 64, 40, 5, None),       # more sink tokens than keys
+    (1, 1, 64, 0, 1, None),         # a single position
+    (3, 5, 64, 1, 1, None),         # window of one token: every query sees itself and the sink token
+    (1, 70, 128, 4, 20, None),      # 128 heads on one latent: a position is four row tiles
+    (1, 90, 96, 2, 30, None),       # 96 heads: a position is three row tiles
 ])
 def test_mla_backward(gpu_device, B, S, Hq, ns, win, block):
     q, k, v, dout = _case(gpu_device, B, S, Hq, 1, 576, 512, alias=True)
@@ -48,6 +52,9 @@ def test_mla_backward(gpu_device, B, S, Hq, ns, win, block):
     (1, 400, 2, 1, True, 32, 64, None),      # aliased values of equal width
     (1, 260, 16, 1, False, 1, 3, 20),        # block-granular, 16 heads per group
     (1, 2500, 1, 1, False, 64, 128, None),   # long enough for several row chunks of the sink tile at G = 1
+    (1, 200, 32, 1, False, 8, 40, None),     # 32 heads per group: one row tile per position
+    (2, 129, 2, 2, True, 0, 128, None),      # window as long as the sequence minus one
+    (1, 64, 4, 2, False, 1, 1, 64),          # one block holds everything
 ])
 def test_d128_backward(gpu_device, B, S, Hq, Hkv, alias, ns, win, block):
     q, k, v, dout = _case(gpu_device, B, S, Hq, Hkv, 128, 128, alias)
