@@ -119,11 +119,17 @@ struct BwdCfg {
     // accumulator blocks (32 columns x 32 items of X) per wave
     static constexpr bool SPLIT_KV = KEYS && !ALIAS;  // half the waves take dK, the other half dV
     static_assert(!SPLIT_KV || DQK == DV, "separate values: equal widths only");
-    // Column blocks of the waves of role 0 and of role 1. Where role 0 carries the most (wide keys,
-    // KEYS: the longer phase 1, the elementwise step, two products per block) it takes one block
-    // fewer: its registers then hold its 36 operand fragments beside its accumulators.
-    static constexpr int NACC0 = SPLIT_KV ? DQK / 32 : DQK / 64 - ((KEYS && DQK == 576) ? 1 : 0);
-    static constexpr int NACC1 = SPLIT_KV ? DQK / 32 : DQK / 32 - NACC0;
+    // Phase 2: every wave accumulates a few column blocks (32 columns) for BOTH blocks of X, so that a
+    // transposed fragment of the streamed tile, once fetched from LDS, feeds two matrix instructions
+    // (fetched once per block of X, LDS bandwidth bounds the kernel). ND0 / ND1: column blocks of a
+    // wave of role 0 / role 1; role 0 (longer phase 1, elementwise step) takes the smaller share.
+    static constexpr int NBLK = DQK / 32;
+    static constexpr int ND0 = SPLIT_KV ? NBLK / 2 : NBLK / 4;
+    static constexpr int ND1 = SPLIT_KV ? (DV / 32) / 2 : (NBLK - 2 * ND0) / 2;
+    static_assert(SPLIT_KV || 2 * ND0 + 2 * ND1 == NBLK, "column blocks must split over the four waves");
+    // of a role-1 wave's blocks, how many also take the second product (dV, columns below d_v)
+    static constexpr int NDBL1 = (KEYS && !SPLIT_KV) ? (DV / 32 - 2 * ND0) / 2 : 0;
+    static_assert(NDBL1 >= 0 && NDBL1 <= ND1, "split of the d_v columns");
     static_assert(DQK % 64 == 0 && DV % 32 == 0 && DV <= DQK, "head widths");
 };
 
@@ -255,6 +261,16 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         xp += lh * 8;
 #pragma unroll
         for (int kk = 0; kk < (ROLE == 0 ? DQK / 16 : DV / 16); ++kk) xf[kk] = *(const bf16x8 *)(xp + kk * 16);
+        // Accumulators and fragments together exceed the 256 AGPRs. Left alone, the allocator treats the
+        // fragments as vector registers it parks in AGPRs, and copies four registers back before every
+        // matrix instruction; told which fragments live in AGPRs for good (a matrix instruction reads
+        // them there) and which in VGPRs, it copies nothing.
+        constexpr int IN_AGPR = (256 - (ROLE == 0 ? C::ND0 : C::ND1) * 32) / 4;
+#pragma unroll
+        for (int kk = 0; kk < (ROLE == 0 ? DQK / 16 : DV / 16); ++kk) {
+            if (kk < IN_AGPR) asm volatile("" : "+a"(xf[kk]));
+            else asm volatile("" : "+v"(xf[kk]));
+        }
     }
     const int w_lo_row = KEYS ? 0 : window_begin_of(x_i, window, block);
     int g_shift = 5;  // KEYS: log2(G) for G < 32, else 5
@@ -324,12 +340,24 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         else if (n < C::NI) copy_1k(tc.b3, yoff[u], tc.dst + n * 1024);
     };
 
-    constexpr int NA = ROLE == 0 ? C::NACC0 : C::NACC1;  // accumulator blocks of this wave
-    f32x16 acc[NA];
+    constexpr int ND = ROLE == 0 ? C::ND0 : C::ND1;  // column blocks of this wave (each for both blocks of X)
+    f32x16 acc[ND][2];
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
+    for (int a = 0; a < ND; ++a)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
+        for (int x2 = 0; x2 < 2; ++x2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][x2][e] = 0.f;
+    // Which column blocks: the two waves of a role (xb = 0, 1) take alternate runs. With a shared
+    // accumulator for dK and dV, blocks below d_v take both products; role 1's blocks are dealt so that
+    // both of its waves get the same number of those (a < NDBL take two products, the rest one).
+    constexpr int NDBL = (KEYS && !C::SPLIT_KV) ? (ROLE == 0 ? ND : C::NDBL1) : 0;
+    auto col_block = [&](int a) {
+        if (C::SPLIT_KV) return xb * ND + a;
+        if (ROLE == 0) return xb * ND + a;
+        if (!KEYS) return 2 * C::ND0 + xb * ND + a;
+        return a < NDBL ? 2 * C::ND0 + xb * NDBL + a : DV / 32 + xb * (ND - NDBL) + (a - NDBL);
+    };
 
     char *region = smem + C::OFF_BUF + xb * C::XREGION;   // dS rows of this block of X, then its p rows
     char *xch = smem + C::OFF_XCH + xb * C::XCH;          // T of this block of X, from its role-1 wave to its role-0 wave
@@ -365,7 +393,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // which costs registers it then finds by spilling -- and a reload from scratch waits for every
         // vector-memory operation in flight, the copy of the next tile included)
         {
-            constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 4, EVERY = NS / COPIES1;
+            constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 8, EVERY = NS / COPIES1;
             // S reads the first streamed tile; T the second when there is one (else the values are the
             // key rows' prefix)
             const char *ya = tile + ((ROLE == 1 && C::HAS_Y2) ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16;
@@ -457,95 +485,100 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         }
         __syncthreads();
 
-        // ---- phase 2: Acc^T[column block][x] += Y^T dS (+ Y2^T p) -----------------------------------
+        // ---- phase 2: Acc^T[column block][x] += Y^T dS (+ Y2^T p), both blocks of X per fragment -------
         {
-            const char *bs = region + ln * C::PROW + lh * 16;
+            const char *b0 = smem + C::OFF_BUF + ln * C::PROW + lh * 16;   // dS rows of block 0 of X ([x][y])
             const char *t1 = tile, *t2 = tile + C::OFF_Y2;
-            {
-                constexpr int HF = ROLE;
-                constexpr int DB0 = (C::SPLIT_KV || HF == 0) ? 0 : C::NACC0;
-                // The matrix instructions of this wave as a flat list of (key step, accumulator, product);
-                // product 1 (Y2^T p, the dV part of a shared accumulator) exists for the first d_v columns
-                // only. Operand fragments are fetched PF entries ahead.
-                constexpr int N2 = (KEYS && !C::SPLIT_KV) ? ((DV / 32 - DB0) < 0 ? 0 : ((DV / 32 - DB0) < NA ? (DV / 32 - DB0) : NA)) : 0;
-                constexpr int PER_KS = NA + N2;            // accumulators a < N2 take two products
-                constexpr int NM = 2 * PER_KS, PF = 3, EVERY = COPIES2 > 0 ? NM / COPIES2 : NM;
-                auto entry = [](int m, int &ks, int &a, int &prod) {
-                    ks = m / PER_KS;
-                    const int r = m % PER_KS;
-                    if (r < 2 * N2) { a = r / 2; prod = r % 2; } else { a = r - N2; prod = 0; }
-                };
-                auto frag = [&](int m) {
-                    int ks, a, prod;
-                    entry(m, ks, a, prod);
-                    if (C::SPLIT_KV) return HF == 0 ? read_transposed(t1, C::ROW1, a, ks, lane) : read_transposed(t2, C::ROW2, a, ks, lane);
-                    return prod == 0 ? read_transposed(t1, C::ROW1, DB0 + a, ks, lane) : read_transposed(t2, C::ROW2, DB0 + a, ks, lane);
-                };
-                bf16x8 b_ds = *(const bf16x8 *)bs, b_p = b_ds;
-                if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW);
-                bf16x8 fr[PF];
+            // The fragments of this wave as a flat list of (key step, column block, product); product 1
+            // (Y2^T p, the dV part of a shared accumulator) exists for the first NDBL blocks. Fetched PF
+            // entries ahead; every fragment feeds one matrix instruction per block of X.
+            constexpr int PER_KS = ND + NDBL;
+            constexpr int NF = 2 * PER_KS, PF = 4, EVERY = COPIES2 > 0 ? (NF / COPIES2 > 0 ? NF / COPIES2 : 1) : NF;
+            auto entry = [](int m, int &ks, int &a, int &prod) {
+                ks = m / PER_KS;
+                const int r = m % PER_KS;
+                if (r < 2 * NDBL) { a = r / 2; prod = r % 2; } else { a = r - NDBL; prod = 0; }
+            };
+            auto frag = [&](int m) {
+                int ks, a, prod;
+                entry(m, ks, a, prod);
+                const bool second = C::SPLIT_KV ? ROLE == 1 : prod == 1;
+                return second ? read_transposed(t2, C::ROW2, col_block(a), ks, lane) : read_transposed(t1, C::ROW1, col_block(a), ks, lane);
+            };
+            bf16x8 b_ds[2], b_p[2];
+            auto load_b = [&](int ks) {
 #pragma unroll
-                for (int m = 0; m < PF && m < NM; ++m) fr[m] = frag(m);
-#pragma unroll
-                for (int m = 0; m < NM; ++m) {
-                    int ks, a, prod;
-                    entry(m, ks, a, prod);
-                    const bool use_p = C::SPLIT_KV ? HF == 1 : prod == 1;
-                    acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[m % PF], use_p ? b_p : b_ds, acc[a], 0, 0, 0);
-                    if (m + PF < NM) fr[m % PF] = frag(m + PF);
-                    if (m == PER_KS - 1) {  // the second key step's dS and p
-                        b_ds = *(const bf16x8 *)(bs + 32);
-                        if (KEYS) b_p = *(const bf16x8 *)(bs + 32 * C::PROW + 32);
-                    }
-                    if (m % EVERY == 0 && m / EVERY < COPIES2 && more) issue_one(tc, COPIES1 + m / EVERY);
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int x2 = 0; x2 < 2; ++x2) {
+                    b_ds[x2] = *(const bf16x8 *)(b0 + x2 * C::XREGION + ks * 32);
+                    b_p[x2] = KEYS ? *(const bf16x8 *)(b0 + x2 * C::XREGION + 32 * C::PROW + ks * 32) : b_ds[x2];
                 }
+            };
+            load_b(0);
+            bf16x8 fr[PF];
+#pragma unroll
+            for (int m = 0; m < PF && m < NF; ++m) fr[m] = frag(m);
+#pragma unroll
+            for (int m = 0; m < NF; ++m) {
+                int ks, a, prod;
+                entry(m, ks, a, prod);
+                const bool use_p = C::SPLIT_KV ? ROLE == 1 : prod == 1;
+                const bf16x8 f = fr[m % PF];
+                acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, use_p ? b_p[0] : b_ds[0], acc[a][0], 0, 0, 0);
+                acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, use_p ? b_p[1] : b_ds[1], acc[a][1], 0, 0, 0);
+                if (m + PF < NF) fr[m % PF] = frag(m + PF);
+                if (m == PER_KS - 1) load_b(1);  // the second key step's dS and p
+                if (m % EVERY == 0 && m / EVERY < COPIES2 && more) issue_one(tc, COPIES1 + m / EVERY);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            // (copies that did not find a slot above)
+#pragma unroll
+            for (int cu = (NF + EVERY - 1) / EVERY; cu < COPIES2; ++cu)
+                if (more) issue_one(tc, COPIES1 + cu);
         }
     }
 
     // ---- epilogue: lane = item of X, 16 values of a block = four runs of four consecutive columns ------
-    if (x_idx >= (KEYS ? S : R)) return;
-    constexpr int hf = ROLE;
-    if (!KEYS) {
-        const int64_t i = x_idx / G;
-        const int hh = (int)(x_idx - i * G);
-        uint16_t *op = p.dq + (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh) * DQK + hf * C::NACC0 * 32 + 4 * lh;
 #pragma unroll
-        for (int a = 0; a < NA; ++a)
+    for (int x2 = 0; x2 < 2; ++x2) {
+        const int64_t xi = (int64_t)xt * 64 + x2 * 32 + ln;
+        if (xi >= (KEYS ? S : R)) continue;
+        if (!KEYS) {
+            const int64_t i = xi / G;
+            const int hh = (int)(xi - i * G);
+            uint16_t *op = p.dq + (((int64_t)b * S + i) * p.Hq + (int64_t)g * G + hh) * DQK + 4 * lh;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                u32x2 w;
-                w[0] = pack_bf16(acc[a][4 * qd], acc[a][4 * qd + 1]);
-                w[1] = pack_bf16(acc[a][4 * qd + 2], acc[a][4 * qd + 3]);
-                *(u32x2 *)(op + a * 32 + qd * 8) = w;
-            }
-    } else {
-        // column of the first accumulator block of this wave in the row [dK (d_qk) | dV (d_v, separate values only)]
-        const int col0 = C::SPLIT_KV ? hf * DQK : hf * C::NACC0 * 32;
-        if (partial) {
+            for (int a = 0; a < ND; ++a)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][x2][4 * qd], acc[a][x2][4 * qd + 1]);
+                    w[1] = pack_bf16(acc[a][x2][4 * qd + 2], acc[a][x2][4 * qd + 3]);
+                    *(u32x2 *)(op + col_block(a) * 32 + qd * 8) = w;
+                }
+        } else if (partial) {
+            // row [dK (d_qk) | dV (d_v, separate values only)] of fp32 partial sums
             constexpr int COLS = C::SPLIT_KV ? DQK + DV : DQK;
             float *op = p.part + ((((int64_t)b * p.Hkv + g) * p.n_sink_kt + xt) * p.max_chunks + chunk) * 64 * COLS +
-                        (int64_t)(xb * 32 + ln) * COLS + col0 + 4 * lh;
+                        (int64_t)(x2 * 32 + ln) * COLS + ((C::SPLIT_KV && ROLE == 1) ? DQK : 0) + 4 * lh;
 #pragma unroll
-            for (int a = 0; a < NA; ++a)
+            for (int a = 0; a < ND; ++a)
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
-                        float4 w;
-                    w.x = acc[a][4 * qd]; w.y = acc[a][4 * qd + 1]; w.z = acc[a][4 * qd + 2]; w.w = acc[a][4 * qd + 3];
-                    *(float4 *)(op + a * 32 + qd * 8) = w;
+                    float4 w;
+                    w.x = acc[a][x2][4 * qd]; w.y = acc[a][x2][4 * qd + 1]; w.z = acc[a][x2][4 * qd + 2]; w.w = acc[a][x2][4 * qd + 3];
+                    *(float4 *)(op + col_block(a) * 32 + qd * 8) = w;
                 }
         } else {
-            const int64_t krow = ((int64_t)b * S + x_idx) * p.Hkv + g;
-            uint16_t *op = (C::SPLIT_KV && hf == 1) ? p.dv + krow * DV + 4 * lh : p.dk + krow * DQK + col0 + 4 * lh;
+            const int64_t krow = ((int64_t)b * S + xi) * p.Hkv + g;
+            uint16_t *op = ((C::SPLIT_KV && ROLE == 1) ? p.dv + krow * DV : p.dk + krow * DQK) + 4 * lh;
 #pragma unroll
-            for (int a = 0; a < NA; ++a)
+            for (int a = 0; a < ND; ++a)
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd) {
-                        u32x2 w;
-                    w[0] = pack_bf16(acc[a][4 * qd], acc[a][4 * qd + 1]);
-                    w[1] = pack_bf16(acc[a][4 * qd + 2], acc[a][4 * qd + 3]);
-                    *(u32x2 *)(op + a * 32 + qd * 8) = w;
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][x2][4 * qd], acc[a][x2][4 * qd + 1]);
+                    w[1] = pack_bf16(acc[a][x2][4 * qd + 2], acc[a][x2][4 * qd + 3]);
+                    *(u32x2 *)(op + col_block(a) * 32 + qd * 8) = w;
                 }
         }
     }
