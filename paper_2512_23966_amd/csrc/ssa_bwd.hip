@@ -380,8 +380,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         const int st = u & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
         __syncthreads();                                  // ... everyone's; tile u - 1 is no longer read
-        const bool more = u + 1 < nt;
-        const TileCopy tc = plan_tile(more ? u + 1 : u, st ^ 1);
+        const TileCopy tc = plan_tile(u + 1 < nt ? u + 1 : u, st ^ 1);
         const char *tile = smem + st * C::STAGE;
 
         // ---- phase 1: one 32 x 32 block of S or T ---------------------------------------------------
@@ -404,7 +403,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             for (int kk = 0; kk < NS; ++kk) {
                 c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % PF], xf[kk], c, 0, 0, 0);
                 if (kk + PF < NS) af[kk % PF] = *(const bf16x8 *)(ya + (kk + PF) * 32);
-                if (kk % EVERY == 0 && kk / EVERY < COPIES1 && more) issue_one(tc, kk / EVERY);
+                if (kk % EVERY == 0 && kk / EVERY < COPIES1 ) issue_one(tc, kk / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -527,16 +526,19 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, use_p ? b_p[1] : b_ds[1], acc[a][1], 0, 0, 0);
                 if (m + PF < NF) fr[m % PF] = frag(m + PF);
                 if (m == PER_KS - 1) load_b(1);  // the second key step's dS and p
-                if (m % EVERY == 0 && m / EVERY < COPIES2 && more) issue_one(tc, COPIES1 + m / EVERY);
+                if (m % EVERY == 0 && m / EVERY < COPIES2 ) issue_one(tc, COPIES1 + m / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // (copies that did not find a slot above)
 #pragma unroll
             for (int cu = (NF + EVERY - 1) / EVERY; cu < COPIES2; ++cu)
-                if (more) issue_one(tc, COPIES1 + cu);
+                issue_one(tc, COPIES1 + cu);
         }
     }
 
+    // (the last iteration copied its own tile once more rather than branch around every copy
+    // instruction; nothing may still be on its way into LDS when the workgroup ends)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     // ---- epilogue: lane = item of X, 16 values of a block = four runs of four consecutive columns ------
 #pragma unroll
     for (int x2 = 0; x2 < 2; ++x2) {

@@ -37,6 +37,7 @@ def _case(device, B, S, Hq, Hkv, d_qk, d_v, alias, seed=0):
     (3, 5, 64, 1, 1, None),         # window of one token: every query sees itself and the sink token
     (1, 70, 128, 4, 20, None),      # 128 heads on one latent: a position is four row tiles
     (1, 90, 96, 2, 30, None),       # 96 heads: a position is three row tiles
+    (1, 300, 64, 2, 2, 64),         # two sink blocks = two key tiles with sink keys, each cut in chunks
 ])
 def test_mla_backward(gpu_device, B, S, Hq, ns, win, block):
     q, k, v, dout = _case(gpu_device, B, S, Hq, 1, 576, 512, alias=True)
@@ -63,6 +64,15 @@ def test_d128_backward(gpu_device, B, S, Hq, Hkv, alias, ns, win, block):
     got = H.run_backward(q, k, v, out, lse, dout, ns, win, scale, block)
     H.compare_backward(q, k, v, out, lse, dout, got, ns, win, scale,
                        f"d128 bwd B{B} S{S} Hq{Hq} Hkv{Hkv} alias{alias} ns{ns} W{win} b{block}", block)
+
+
+def test_mla_backward_two_latent_heads(gpu_device):
+    B, S, Hq, Hkv, ns, win = 2, 70, 128, 2, 4, 20
+    q, k, v, dout = _case(gpu_device, B, S, Hq, Hkv, 576, 512, alias=True, seed=30)
+    scale = 192 ** -0.5
+    out, lse = H.oracle_forward_all(q, k, v, ns, win, scale, 512)
+    got = H.run_backward(q, k, v, out, lse, dout, ns, win, scale)
+    H.compare_backward(q, k, v, out, lse, dout, got, ns, win, scale, "mla bwd two latent heads")
 
 
 def test_backward_after_the_hip_forward(gpu_device):
