@@ -107,5 +107,4 @@ if __name__ == "__main__":
     for dqk in (576, 128):
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
-    print(macro_copy(576, 9, 4, " nt"))
     print("#endif")

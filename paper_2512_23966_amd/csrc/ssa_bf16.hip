@@ -69,11 +69,14 @@ struct TileCfg {
     static constexpr int KCPR = KROW / 16;       // 16-byte chunks per padded key row
     static constexpr int VCPR = VROW / 16;
     // global -> LDS copy: one instruction moves 64 consecutive 16-byte chunks (1 KB) of the padded
-    // tile; instruction i belongs to wave i % NW
+    // tile; instruction i belongs to copying wave i % NCW. Prefill: all four waves copy. Decode: the
+    // two value waves do (their matrix instructions leave them idle a third of the time, while the
+    // scoring waves pace the loop).
+    static constexpr int NCW = SPEC ? VW : NW;
     static constexpr int K_INSTR = (N * KCPR + 63) / 64;
     static constexpr int V_INSTR = ALIAS ? 0 : (N * VCPR + 63) / 64;
-    static constexpr int K_PER_WAVE = (K_INSTR + NW - 1) / NW;
-    static constexpr int V_PER_WAVE = (V_INSTR + NW - 1) / NW;
+    static constexpr int K_PER_WAVE = (K_INSTR + NCW - 1) / NCW;
+    static constexpr int V_PER_WAVE = (V_INSTR + NCW - 1) / NCW;
     static constexpr int KTILE = K_INSTR * 1024;
     static constexpr int VTILE = V_INSTR * 1024;
     static constexpr int STAGE = KTILE + VTILE;
@@ -81,7 +84,7 @@ struct TileCfg {
     // flight. Decode is bound by HBM latency x bandwidth, so it keeps one more tile in flight.
     static constexpr int NSTAGE = DECODE ? 4 : 3;
     // copy instructions one wave issues per tile, at least (waves differ by at most one)
-    static constexpr int MIN_COPIES = K_INSTR / NW + V_INSTR / NW;
+    static constexpr int MIN_COPIES = K_INSTR / NCW + V_INSTR / NCW;
     // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer pair
     static constexpr int NPBUF = 2 * (PRECISE ? 2 : 1);
     static constexpr int PLO = 2;                // index offset of the low-term buffers
@@ -109,6 +112,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const bool scorer = !SPEC || wave < RB;   // this wave scores row block `wr` and runs its softmax
     const int wr = scorer ? wave : 0;
     const int vw = SPEC ? wave - RB : wave;   // which slice of the output columns this wave accumulates
+    const bool copier = !SPEC || !scorer;     // this wave issues tile copies
+    const int cw = SPEC ? (scorer ? 0 : vw) : wave;  // its index among the copying waves
+    constexpr int NCW = C::NCW;
 
     // ---- which tile of which (batch, kv head) ------------------------------------------------
     int id = blockIdx.x;
@@ -205,10 +211,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
     uint32_t kvoff[C::K_PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(u * NW + wave, C::KCPR, pos_stride_k);
+    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(u * NCW + cw, C::KCPR, pos_stride_k);
     uint32_t vvoff[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
 #pragma unroll
-    for (int u = 0; u < C::V_PER_WAVE; ++u) vvoff[u] = copy_offset(u * NW + wave, C::VCPR, pos_stride_v);
+    for (int u = 0; u < C::V_PER_WAVE; ++u) vvoff[u] = copy_offset(u * NCW + cw, C::VCPR, pos_stride_v);
 
     const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
     // A paged cache (decode only) keeps the rows of a sequence in pages of 2^page_shift rows that a
@@ -260,35 +266,45 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             asm volatile("s_mov_b32 m0, %2\n s_nop 0\n global_load_lds_dwordx4 %0, %1"
                          :: "v"(off), "s"(base), "s"(lds_addr) : "memory", "m0");
     };
-    // this wave's copy instructions [u_first, ...) of key tile t, which starts at cache row `row`,
-    // into `stage`
-    auto issue_tile = [&](int t, int stage, int u_first, int64_t row) {
+    // what the copy instructions of one key tile share (wave-uniform): the tile starts at cache row `row`
+    struct TileCopy {
+        const char *ksrc, *vsrc;
+        uint32_t kdst, vdst, kmax, vmax;
+    };
+    auto plan_copy = [&](int t, int stage, int64_t row) {
         const int64_t j0 = (int64_t)key_tile(t) * N;
         // rows of the tile at or past the sequence end fetch from its last valid row instead:
         // they are dead (j > i) and only have to be finite
         const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
-        const char *ksrc = kbase + row * (int64_t)pos_stride_k;
-        const uint32_t kdst = smem_lds + stage * C::STAGE + wave * 1024;
-        const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
-#pragma unroll
-        for (int u = 0; u < C::K_PER_WAVE; ++u) {
-            if (u >= u_first && ((u + 1) * NW <= C::K_INSTR || u * NW + wave < C::K_INSTR)) {  // wave-uniform
-                const uint32_t off = kvoff[u] < kmax ? kvoff[u] : kmax;
-                copy_1k(ksrc, off, kdst + u * (NW * 1024));
-            }
+        TileCopy tc;
+        tc.ksrc = kbase + row * (int64_t)pos_stride_k;
+        tc.kdst = smem_lds + stage * C::STAGE + cw * 1024;
+        tc.kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
+        tc.vsrc = vbase + row * (int64_t)pos_stride_v;
+        tc.vdst = smem_lds + stage * C::STAGE + C::KTILE + cw * 1024;
+        tc.vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
+        return tc;
+    };
+    // copy instruction c of this wave: its key copies first, then (separate values) its value copies
+    constexpr int COPIES_PER_WAVE = C::K_PER_WAVE + C::V_PER_WAVE;
+    auto copy_nth = [&](const TileCopy &tc, int c) {
+        if (c < C::K_PER_WAVE) {
+            const int u = c;
+            if ((u + 1) * NCW <= C::K_INSTR || u * NCW + cw < C::K_INSTR)  // wave-uniform
+                copy_1k(tc.ksrc, kvoff[u] < tc.kmax ? kvoff[u] : tc.kmax, tc.kdst + u * (NCW * 1024));
+        } else if (!ALIAS) {
+            const int u = c - C::K_PER_WAVE;
+            if ((u + 1) * NCW <= C::V_INSTR || u * NCW + cw < C::V_INSTR)
+                copy_1k(tc.vsrc, vvoff[u] < tc.vmax ? vvoff[u] : tc.vmax, tc.vdst + u * (NCW * 1024));
         }
-        if (!ALIAS) {
-            const char *vsrc = vbase + row * (int64_t)pos_stride_v;
-            const uint32_t vdst = smem_lds + stage * C::STAGE + C::KTILE + wave * 1024;
-            const uint32_t vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
+    };
+    // this wave's copy instructions [c_first, ...) of key tile t into `stage`
+    auto issue_tile = [&](int t, int stage, int c_first, int64_t row) {
+        if (!copier) return;
+        const TileCopy tc = plan_copy(t, stage, row);
 #pragma unroll
-            for (int u = 0; u < C::V_PER_WAVE; ++u) {
-                if ((u + 1) * NW <= C::V_INSTR || u * NW + wave < C::V_INSTR) {
-                    const uint32_t off = vvoff[u] < vmax ? vvoff[u] : vmax;
-                    copy_1k(vsrc, off, vdst + u * (NW * 1024));
-                }
-            }
-        }
+        for (int c = 0; c < COPIES_PER_WAVE; ++c)
+            if (c >= c_first) copy_nth(tc, c);
     };
 
     f32x16 o[C::DVB][RB];
@@ -314,7 +330,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // One inline-asm statement (score_asm.h): key fragment kk + DEPTH is fetched from LDS while
     // fragment kk feeds the matrix core, with the exact lgkmcnt each step needs. The accumulator is
     // in VGPRs (the AGPR half of the register file is full of O).
-    constexpr bool WEAVE = (DQK == 576 && ALIAS);  // copy instructions woven into the score phase
+    constexpr bool WEAVE = (DQK == 576 && ALIAS && !DECODE);  // copy instructions woven into the score phase (prefill)
     // The same with the copy of key tile `t_copy` into stage `stage_copy` woven in (wide rows only):
     // the copy instructions issue between matrix instructions instead of ahead of them.
     auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy, int64_t row_copy) {
@@ -328,8 +344,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             static_assert(!WEAVE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
             uint32_t tmp;
-            if constexpr (DECODE) LOZA_SCORE_PHASE_576_COPY_W4_NT(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
-            else LOZA_SCORE_PHASE_576_COPY_W4(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
+            LOZA_SCORE_PHASE_576_COPY_W4(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
         }
     };
     auto score_tile = [&](int stage, f32x16 &s) {
@@ -509,7 +524,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         if (V_NSTEP > 1) load_v(vp, 1, f.vlo[1], f.vhi[1]);
     };
     auto value_tile = [&](const int stage, const int pbuf, ValueFrags &f, auto with_softmax, f32x16 &s,
-                          const int j0_next, const int pbuf_next, const float lazy) {
+                          const int j0_next, const int pbuf_next, const float lazy, auto &&after_slot) {
         constexpr bool WITH_SOFTMAX = decltype(with_softmax)::value;
         constexpr int KS = V_KS, NSTEP = V_NSTEP;
         const char *vp, *pb;
@@ -547,6 +562,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                     for (int jj = 0; jj < JPS; ++jj)
                         if (slot * JPS + jj < SM_JOBS) sm_job(slot * JPS + jj, s, j0_next, lazy, pbuf_next);
                 }
+                after_slot(slot, NSLOT);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -619,27 +635,19 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
             rescale_tile(u & 1, flags);
             value_tile(st_v, u & 1, vf, std::true_type{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff,
-                       (u + 1) & 1, u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
+                       (u + 1) & 1, u + 1 < p.exact_tiles ? 0.f : p.lazy_log2, [](int, int) {});
             st_v = st_k;
         }
     } else if (scorer) {
         // scoring role: while the value waves work on tile u, take the scores of tile u + 1 and hand
-        // its P over through LDS
+        // its P over through LDS (score phase and softmax of a tile pace the loop: these waves issue
+        // no copies)
+        page_wait(page_pre);
         int st_v = 0;
         for (int u = 0; u < nt; ++u) {
             top_of_tile(u);
-            const int64_t row_now = tile_row(tile_ahead(u), page_wait(page_pre));
-            page_pre = page_request(tile_ahead(u + 1));
             const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
-            const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
-            const bool more = u + AHEAD < nt;
-            if (WEAVE && more) {
-                score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l, row_now);
-                issue_tile(t_begin + u + AHEAD, st_l, WOVEN, row_now);
-            } else {
-                if (more) issue_tile(t_begin + u + AHEAD, st_l, 0, row_now);
-                score_tile(st_k, s);
-            }
+            score_tile(st_k, s);
             softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
                          u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
             st_v = st_k;
@@ -655,9 +663,17 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             const u32x4 flags = rescale_flags(u & 1);
             ValueFrags vf;
             value_prefetch(st_v, u & 1, vf);
-            if (u + AHEAD < nt) issue_tile(t_begin + u + AHEAD, st_l, 0, row_now);
+            // the copies of tile u + AHEAD go out between the matrix instructions of this value phase
+            // (all at once they fill the memory pipeline's queue and stall the wave)
+            const bool more = u + AHEAD < nt;
+            const TileCopy tc = plan_copy(more ? t_begin + u + AHEAD : t_begin + u, st_l, row_now);
             rescale_tile(u & 1, flags);
-            value_tile(st_v, u & 1, vf, std::false_type{}, s, 0, 0, 0.f);
+            value_tile(st_v, u & 1, vf, std::false_type{}, s, 0, 0, 0.f, [&](int slot, int n_slots) {
+                const int per_slot = (COPIES_PER_WAVE + n_slots - 1) / n_slots;
+#pragma unroll
+                for (int c = slot * per_slot; c < (slot + 1) * per_slot; ++c)
+                    if (c < COPIES_PER_WAVE && more) copy_nth(tc, c);
+            });
             st_v = st_v + 1 < NSTAGE ? st_v + 1 : 0;
         }
     }
