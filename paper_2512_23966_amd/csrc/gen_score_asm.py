@@ -83,8 +83,7 @@ def macro_copy(dqk: int, n_copy: int, waves: int, hint: str = "") -> str:
     text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY_W{waves}{suffix}(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
     text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, waves, hint).splitlines(True))
     text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\")\n"
-    if not hint:
-        text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
+    text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
     return text
 
 
@@ -107,4 +106,5 @@ if __name__ == "__main__":
     for dqk in (576, 128):
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
+    print(macro_copy(576, 4, 2, " nt"))
     print("#endif")

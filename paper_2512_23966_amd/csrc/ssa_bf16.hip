@@ -69,14 +69,18 @@ struct TileCfg {
     static constexpr int KCPR = KROW / 16;       // 16-byte chunks per padded key row
     static constexpr int VCPR = VROW / 16;
     // global -> LDS copy: one instruction moves 64 consecutive 16-byte chunks (1 KB) of the padded
-    // tile; instruction i belongs to copying wave i % NCW. Prefill: all four waves copy. Decode: the
-    // two value waves do (their matrix instructions leave them idle a third of the time, while the
-    // scoring waves pace the loop).
-    static constexpr int NCW = SPEC ? VW : NW;
+    // tile. Prefill: instruction i belongs to wave i % 4. Decode: the scoring waves pace the loop and
+    // the value waves have time to spare, so the value waves take most copies (between their matrix
+    // instructions): the first 2 SC key instructions alternate between the two scoring waves (SC
+    // each, woven into their score phase; wide aliased rows only), the rest alternates between the
+    // two value waves.
+    static constexpr int NCW = SPEC ? VW : NW;   // waves a run of instructions alternates between
     static constexpr int K_INSTR = (N * KCPR + 63) / 64;
     static constexpr int V_INSTR = ALIAS ? 0 : (N * VCPR + 63) / 64;
-    static constexpr int K_PER_WAVE = (K_INSTR + NCW - 1) / NCW;
+    static constexpr int SC = (SPEC && DQK == 576 && ALIAS) ? LOZA_SCORE_COPIES_576_W2 : 0;
+    static constexpr int K_PER_WAVE = (K_INSTR - 2 * SC + NCW - 1) / NCW;   // of a value wave in decode; SC <= this
     static constexpr int V_PER_WAVE = (V_INSTR + NCW - 1) / NCW;
+    static_assert(SC <= K_PER_WAVE, "the copy offsets of a scoring wave share the array of a value wave");
     static constexpr int KTILE = K_INSTR * 1024;
     static constexpr int VTILE = V_INSTR * 1024;
     static constexpr int STAGE = KTILE + VTILE;
@@ -84,7 +88,7 @@ struct TileCfg {
     // flight. Decode is bound by HBM latency x bandwidth, so it keeps one more tile in flight.
     static constexpr int NSTAGE = DECODE ? 4 : 3;
     // copy instructions one wave issues per tile, at least (waves differ by at most one)
-    static constexpr int MIN_COPIES = K_INSTR / NCW + V_INSTR / NCW;
+    static constexpr int MIN_COPIES = (K_INSTR - 2 * SC) / NCW + V_INSTR / NCW;
     // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer pair
     static constexpr int NPBUF = 2 * (PRECISE ? 2 : 1);
     static constexpr int PLO = 2;                // index offset of the low-term buffers
@@ -112,9 +116,11 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const bool scorer = !SPEC || wave < RB;   // this wave scores row block `wr` and runs its softmax
     const int wr = scorer ? wave : 0;
     const int vw = SPEC ? wave - RB : wave;   // which slice of the output columns this wave accumulates
-    const bool copier = !SPEC || !scorer;     // this wave issues tile copies
-    const int cw = SPEC ? (scorer ? 0 : vw) : wave;  // its index among the copying waves
     constexpr int NCW = C::NCW;
+    const int cw = SPEC ? (scorer ? wave : vw) : wave;               // index within the waves it alternates with
+    const int k_first = (SPEC && !scorer) ? 2 * C::SC : 0;             // first key instruction of that run
+    const int k_count_max = (SPEC && scorer) ? C::SC : C::K_PER_WAVE;  // key instructions of this wave, at most
+    const bool copies_values = !SPEC || !scorer;
 
     // ---- which tile of which (batch, kv head) ------------------------------------------------
     int id = blockIdx.x;
@@ -211,7 +217,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
     uint32_t kvoff[C::K_PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(u * NCW + cw, C::KCPR, pos_stride_k);
+    for (int u = 0; u < C::K_PER_WAVE; ++u) kvoff[u] = copy_offset(k_first + u * NCW + cw, C::KCPR, pos_stride_k);
     uint32_t vvoff[C::V_PER_WAVE > 0 ? C::V_PER_WAVE : 1];
 #pragma unroll
     for (int u = 0; u < C::V_PER_WAVE; ++u) vvoff[u] = copy_offset(u * NCW + cw, C::VCPR, pos_stride_v);
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
         TileCopy tc;
         tc.ksrc = kbase + row * (int64_t)pos_stride_k;
-        tc.kdst = smem_lds + stage * C::STAGE + cw * 1024;
+        tc.kdst = smem_lds + stage * C::STAGE + (k_first + cw) * 1024;
         tc.kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
         tc.vsrc = vbase + row * (int64_t)pos_stride_v;
         tc.vdst = smem_lds + stage * C::STAGE + C::KTILE + cw * 1024;
@@ -290,17 +296,16 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     auto copy_nth = [&](const TileCopy &tc, int c) {
         if (c < C::K_PER_WAVE) {
             const int u = c;
-            if ((u + 1) * NCW <= C::K_INSTR || u * NCW + cw < C::K_INSTR)  // wave-uniform
+            if (u < k_count_max && k_first + u * NCW + cw < C::K_INSTR)  // wave-uniform
                 copy_1k(tc.ksrc, kvoff[u] < tc.kmax ? kvoff[u] : tc.kmax, tc.kdst + u * (NCW * 1024));
         } else if (!ALIAS) {
             const int u = c - C::K_PER_WAVE;
-            if ((u + 1) * NCW <= C::V_INSTR || u * NCW + cw < C::V_INSTR)
+            if (copies_values && u * NCW + cw < C::V_INSTR)
                 copy_1k(tc.vsrc, vvoff[u] < tc.vmax ? vvoff[u] : tc.vmax, tc.vdst + u * (NCW * 1024));
         }
     };
     // this wave's copy instructions [c_first, ...) of key tile t into `stage`
     auto issue_tile = [&](int t, int stage, int c_first, int64_t row) {
-        if (!copier) return;
         const TileCopy tc = plan_copy(t, stage, row);
 #pragma unroll
         for (int c = 0; c < COPIES_PER_WAVE; ++c)
@@ -330,7 +335,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // One inline-asm statement (score_asm.h): key fragment kk + DEPTH is fetched from LDS while
     // fragment kk feeds the matrix core, with the exact lgkmcnt each step needs. The accumulator is
     // in VGPRs (the AGPR half of the register file is full of O).
-    constexpr bool WEAVE = (DQK == 576 && ALIAS && !DECODE);  // copy instructions woven into the score phase (prefill)
+    constexpr bool WEAVE = (DQK == 576 && ALIAS);  // copy instructions woven into the score phase
     // The same with the copy of key tile `t_copy` into stage `stage_copy` woven in (wide rows only):
     // the copy instructions issue between matrix instructions instead of ahead of them.
     auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy, int64_t row_copy) {
@@ -341,10 +346,13 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             const char *ksrc = kbase + row_copy * (int64_t)pos_stride_k;
             const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
             const uint32_t m0base = smem_lds + stage_copy * C::STAGE + wave * 1024;
-            static_assert(!WEAVE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
+            static_assert(!WEAVE || DECODE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
             uint32_t tmp;
-            LOZA_SCORE_PHASE_576_COPY_W4(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
+            // prefill: 9 of this wave's 9 or 10 copies, every fourth instruction of the tile; decode: the
+            // 4 copies of a scoring wave, every second of the first eight, marked as read-once
+            if constexpr (DECODE) LOZA_SCORE_PHASE_576_COPY_W2_NT(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
+            else LOZA_SCORE_PHASE_576_COPY_W4(s, kf, tmp, kaddr, qf, kvoff, kmax, ksrc, m0base);
         }
     };
     auto score_tile = [&](int stage, f32x16 &s) {
@@ -593,8 +601,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             for (int kk = 0; kk < DQK / 16; ++kk) qf[kk] = *(const bf16x8 *)(qp + kk * 16);
         }
         // tile 0 has landed when at most the copies of the later ones are outstanding
-        if (nt >= AHEAD) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 1) * C::MIN_COPIES));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        if (nt < AHEAD) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        else if (SPEC && scorer) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 1) * C::SC));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 1) * C::MIN_COPIES));
         lds_barrier();
         if (scorer) {
             score_tile(0, s);
@@ -605,6 +614,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         // this wave's share of tile u + 1 has landed when at most the copies of the tiles after it
         // are outstanding
         if (u + AHEAD > nt) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        else if (SPEC && scorer) __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 2) * C::SC));
         else __builtin_amdgcn_s_waitcnt(vmcnt_imm((AHEAD - 2) * C::MIN_COPIES));
         lds_barrier();  // ... everyone's; P of tile u is visible; the stage of tile u - 1 is free
     };
@@ -641,13 +651,16 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     } else if (scorer) {
         // scoring role: while the value waves work on tile u, take the scores of tile u + 1 and hand
         // its P over through LDS (score phase and softmax of a tile pace the loop: these waves issue
-        // no copies)
-        page_wait(page_pre);
+        // only the few copies that fit between their matrix instructions at no cost)
         int st_v = 0;
         for (int u = 0; u < nt; ++u) {
             top_of_tile(u);
+            const int64_t row_now = tile_row(tile_ahead(u), page_wait(page_pre));
+            page_pre = page_request(tile_ahead(u + 1));
             const int st_k = st_v + 1 < NSTAGE ? st_v + 1 : 0;
-            score_tile(st_k, s);
+            const int st_l = st_v == 0 ? NSTAGE - 1 : st_v - 1;
+            if (WEAVE && u + AHEAD < nt) score_tile_copy(st_k, s, t_begin + u + AHEAD, st_l, row_now);
+            else score_tile(st_k, s);
             softmax_tile(s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff, (u + 1) & 1,
                          u + 1 < p.exact_tiles ? 0.f : p.lazy_log2);
             st_v = st_k;
