@@ -12,8 +12,8 @@
 // extend and decode can read a paged cache through a block table.
 //
 // How it is mapped to the machine (one workgroup = 4 wavefronts = 1 per SIMD; prefill tiles hold
-// 128 query rows and all four waves score, decode tiles hold 64 rows (the heads of one token) and
-// two waves score while all four accumulate values):
+// 128 query rows and all four waves score and accumulate, decode tiles hold 64 rows (the heads of one
+// token) and two waves score while the other two accumulate values and issue most tile copies):
 //   * Rows of a workgroup tile are (position, head-in-group) pairs of ONE key/value head, so all
 //     query heads that share a latent (absorbed MLA) reuse each key tile from a single LDS copy.
 //   * Only live key tiles are enumerated: the sink tiles, then the window tiles, by closed-form

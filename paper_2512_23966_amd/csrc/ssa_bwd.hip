@@ -26,9 +26,12 @@
 //               T handed to the S waves through LDS, which form p and dS and leave them, as bf16,
 //               in LDS ([x][y], y contiguous);
 //     phase 2:  Acc^T[d][x] += Y^T[d][y] dS[y][x]  (and += Y2^T p for dV), all four waves, each
-//               owning one block of X and half of the column blocks; the streamed tile is read
-//               transposed from LDS (ds_read_b64_tr_b16) as the forward's value phase does.
-// The streamed tiles travel global -> LDS with global_load_lds_dwordx4 into a ring of two stages.
+//               owning a few blocks of 32 columns for both blocks of X; the streamed tile is read
+//               transposed from LDS (ds_read_b64_tr_b16) as the forward's value phase does, and
+//               every fragment read feeds two matrix instructions.
+// The streamed tiles travel global -> LDS with global_load_lds_dwordx4 into a ring of two stages,
+// the copy instructions of the next tile issued between the matrix instructions of both phases.
+// After the setup the two roles run separate instantiations of the tile loop.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
