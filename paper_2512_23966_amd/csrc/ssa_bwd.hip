@@ -22,9 +22,9 @@
 // Both forms of the main kernel are the same program with the roles of rows and keys exchanged:
 //   stationary side X (two blocks of 32), streamed side Y (tiles of 32), and per tile
 //     phase 1:  S[y][x] = Y1 X1^T (contraction d_qk)   and   T[y][x] = Y2 X2^T (contraction d_v)
-//               on different wavefronts (S: waves 0, 1; T: waves 2, 3; one block of X each),
-//               T handed to the S waves through LDS, which form p and dS and leave them, as bf16,
-//               in LDS ([x][y], y contiguous);
+//               on different wavefronts (S: waves 0, 1; T: waves 2, 3; one block of X each); the
+//               two waves of a block swap halves of their results through LDS and each forms p
+//               and dS for its half, left as bf16 in LDS ([x][y], y contiguous);
 //     phase 2:  Acc^T[d][x] += Y^T[d][y] dS[y][x]  (and += Y2^T p for dV), all four waves, each
 //               owning a few blocks of 32 columns for both blocks of X; the streamed tile is read
 //               transposed from LDS (ds_read_b64_tr_b16) as the forward's value phase does, and
@@ -125,7 +125,7 @@ struct BwdCfg {
     // Phase 2: every wave accumulates a few column blocks (32 columns) for BOTH blocks of X, so that a
     // transposed fragment of the streamed tile, once fetched from LDS, feeds two matrix instructions
     // (fetched once per block of X, LDS bandwidth bounds the kernel). ND0 / ND1: column blocks of a
-    // wave of role 0 / role 1; role 0 (longer phase 1, elementwise step) takes the smaller share.
+    // wave of role 0 / role 1; role 0 (longer phase 1, four more operand fragments) takes the smaller share.
     static constexpr int NBLK = DQK / 32;
     static constexpr int ND0 = SPLIT_KV ? NBLK / 2 : NBLK / 4;
     static constexpr int ND1 = SPLIT_KV ? (DV / 32) / 2 : (NBLK - 2 * ND0) / 2;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     const uint32_t smem_lds = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-    const int xb = wave & 1, role = wave >> 1;  // role 0: S = Y1 X1^T and the elementwise step; role 1: T = Y2 X2^T
+    const int xb = wave & 1, role = wave >> 1;  // role 0: S = Y1 X1^T; role 1: T = Y2 X2^T; the elementwise step is shared
     const int G = p.G;
     const int64_t S = p.S, R = S * G;
     const int n_sink = p.n_sink, window = p.window, block = p.block;
@@ -234,8 +234,8 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         return yt < yt_wrap ? yt : yt - nt;
     };
 
-    // From here on the two roles run separate instantiations of the same code (role 0: S = Y1 X1^T and
-    // the elementwise step; role 1: T = Y2 X2^T): each then has registers for its own operand fragments
+    // From here on the two roles run separate instantiations of the same code (role 0: S = Y1 X1^T;
+    // role 1: T = Y2 X2^T): each then has registers for its own operand fragments
     // and its own share of the accumulators, and no branch on the role sits inside the tile loop. The
     // workgroup barriers of the two instantiations pair up one to one.
     auto run = [&](auto role_c) {
@@ -410,20 +410,23 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if constexpr (ROLE == 1) {
+        // The elementwise step is shared: of this lane's four runs of four values, the S wave processes
+        // runs 0, 1 and the T wave runs 2, 3; each hands the other the half of its block it does not
+        // process itself (xch: [role of the writer][run][lane] x 16 bytes).
+        constexpr int QD_OWN = ROLE == 0 ? 0 : 2, QD_GIVE = ROLE == 0 ? 2 : 0;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                float4 w;
-                w.x = c[4 * qd]; w.y = c[4 * qd + 1]; w.z = c[4 * qd + 2]; w.w = c[4 * qd + 3];
-                *(float4 *)(xch + (qd * 64 + lane) * 16) = w;
-            }
+        for (int q2 = 0; q2 < 2; ++q2) {
+            const int qd = QD_GIVE + q2;
+            float4 w;
+            w.x = c[4 * qd]; w.y = c[4 * qd + 1]; w.z = c[4 * qd + 2]; w.w = c[4 * qd + 3];
+            *(float4 *)(xch + ((ROLE * 2 + q2) * 64 + lane) * 16) = w;
         }
         __syncthreads();
 
         // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
         // four values at a time: this lane's 16 values are four runs of four consecutive y, and a run
         // is one 8-byte store into the [x][y] buffers (y contiguous)
-        if constexpr (ROLE == 0) {
+        {
             const int y0 = y_tile(u) * 32;
             char *ps = region + ln * C::PROW + (4 * lh) * 2;
             const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
@@ -445,9 +448,10 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             auto elementwise = [&](auto masked) {
             constexpr bool MASKED = decltype(masked)::value;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const float4 t4 = *(const float4 *)(xch + (qd * 64 + lane) * 16);
-                const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
+            for (int q2 = 0; q2 < 2; ++q2) {
+                const int qd = QD_OWN + q2;
+                const float4 o4 = *(const float4 *)(xch + (((1 - ROLE) * 2 + q2) * 64 + lane) * 16);
+                const float other[4] = {o4.x, o4.y, o4.z, o4.w};   // the other wave's block: T for the S wave, S for the T wave
                 float pv[4], dsv[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -467,9 +471,10 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                             ok = (y0 + y < (int)R) & (j < (int)S) & (j <= i) & ((j < n_sink) | (j >= w_lo));
                         }
                     }
-                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(c[e], p.scale_log2, -lse2));
+                    const float sv = ROLE == 0 ? c[e] : other[t], tv = ROLE == 0 ? other[t] : c[e];
+                    const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, p.scale_log2, -lse2));
                     pv[t] = ok ? pe : 0.f;
-                    dsv[t] = ok ? p.scale * pe * (tt[t] - D) : 0.f;
+                    dsv[t] = ok ? p.scale * pe * (tv - D) : 0.f;
                 }
                 u32x2 w;
                 w[0] = pack_bf16(dsv[0], dsv[1]);
