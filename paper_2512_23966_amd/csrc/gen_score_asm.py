@@ -62,6 +62,8 @@ def body_copy(ks: int, depth: int, n_copy: int, waves: int, hint: str = "") -> s
             lines.append(f"ds_read_b128 {t(kk % depth)}, {addr} offset:{(kk + depth) * 32}")
         if c < n_copy and kk % every == every // 2:
             lines.append(f"v_min_u32 {tmp}, {kmax}, {voff(c)}")
+            # (the scalar add also writes SCC: the statement names it as clobbered, or a compare the
+            # compiler made before the statement and selects on after it reads the add's carry)
             lines.append(f"s_add_u32 m0, {m0b}, {c * waves * 1024}")
             lines.append("s_nop 0")
             lines.append(f"global_load_lds_dwordx4 {tmp}, {src}{hint}")
@@ -82,8 +84,25 @@ def macro_copy(dqk: int, n_copy: int, waves: int, hint: str = "") -> str:
     text += f" (cache policy:{hint})\n" if hint else "\n"
     text += f"#define LOZA_SCORE_PHASE_{dqk}_COPY_W{waves}{suffix}(s_, kf_, tmp_, addr_, qf_, voff_, kmax_, src_, m0base_) \\\n    asm volatile( \\\n"
     text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, waves, hint).splitlines(True))
-    text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\")\n"
+    text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\", \"scc\")\n"
     text += f"#define LOZA_SCORE_COPIES_{dqk}_W{waves} {n_copy}\n"
+    return text
+
+
+def macro_bwd(ks: int, n_copy: int, n_agpr: int) -> str:
+    """Phase 1 of the backward kernels: the same statement (ks k-steps, n_copy woven copies, four
+    waves), with the first n_agpr stationary fragments read from AGPRs (the rest from VGPRs): there
+    the accumulators leave part of the AGPR file free and the fragments that fit live in it."""
+    depth = min(DEPTH, ks)
+    outs = ['"=&v"(s_)'] + [f'"=&v"(kf_[{d}])' for d in range(depth)] + ['"=&v"(tmp_)']
+    ins = ['"v"(addr_)'] + [f'"{"a" if kk < n_agpr else "v"}"(xf_[{kk}])' for kk in range(ks)]
+    ins += [f'"v"(voff_[{c}])' for c in range(n_copy)] + ['"s"(max_)', '"s"(src_)', '"s"(m0base_)']
+    text = f"// backward, phase 1: {ks} k-steps, {n_copy} woven copies, fragments 0..{n_agpr - 1} in AGPRs\n"
+    text += f"#define LOZA_BWD_PHASE1_K{ks}_C{n_copy}_A{n_agpr}(s_, kf_, tmp_, addr_, xf_, voff_, max_, src_, m0base_) \\\n    asm volatile( \\\n"
+    # (the waits inside count this statement's own LDS reads: nothing else may be outstanding)
+    text += '    "s_waitcnt lgkmcnt(0)\\n" \\\n'
+    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, 4).splitlines(True))
+    text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\", \"scc\")\n"
     return text
 
 
@@ -107,4 +126,6 @@ if __name__ == "__main__":
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
     print(macro_copy(576, 4, 2, " nt"))
+    for ks, n_copy, n_agpr in ((36, 9, 32), (32, 9, 24), (36, 5, 32), (32, 5, 24)):
+        print(macro_bwd(ks, n_copy, n_agpr))
     print("#endif")

@@ -37,6 +37,7 @@
 
 #include <type_traits>
 
+#include "score_asm.h"
 #include "ssa_device.h"
 #include "ssa_kernels.h"
 
@@ -242,6 +243,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     constexpr int ROLE = decltype(role_c)::value;
     // ---- the stationary side: matrix-core B operands in registers --------------------------------
     bf16x8 xf[ROLE == 0 ? DQK / 16 : DV / 16];
+    constexpr int IN_AGPR = (256 - (ROLE == 0 ? C::ND0 : C::ND1) * 32) / 4;  // fragments that live in AGPRs
     const int64_t x_idx = (int64_t)xt * 64 + xb * 32 + ln;          // row (i * G + head) or key
     const int64_t x_c = x_idx < (KEYS ? S : R) ? x_idx : (KEYS ? S : R) - 1;
     int x_i = 0;                                                     // !KEYS: position of this lane's row
@@ -268,7 +270,6 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // fragments as vector registers it parks in AGPRs, and copies four registers back before every
         // matrix instruction; told which fragments live in AGPRs for good (a matrix instruction reads
         // them there) and which in VGPRs, it copies nothing.
-        constexpr int IN_AGPR = (256 - (ROLE == 0 ? C::ND0 : C::ND1) * 32) / 4;
 #pragma unroll
         for (int kk = 0; kk < (ROLE == 0 ? DQK / 16 : DV / 16); ++kk) {
             if (kk < IN_AGPR) asm volatile("" : "+a"(xf[kk]));
@@ -388,6 +389,30 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
 
         // ---- phase 1: one 32 x 32 block of S or T ---------------------------------------------------
         f32x16 c;
+        // S reads the first streamed tile; T the second when there is one (else the values are the key
+        // rows' prefix)
+        constexpr int A_OFF = (ROLE == 1 && C::HAS_Y2) ? C::OFF_Y2 : 0, A_ROW = (ROLE == 1 && C::HAS_Y2) ? C::ROW2 : C::ROW1;
+        constexpr bool WIDE = (DQK == 576 && DV == 512);
+        if constexpr (WIDE) {
+            // Wide rows: the whole phase is one generated asm statement (score_asm.h), as the forward's
+            // score phase is: fragment kk + 6 is fetched from LDS while fragment kk feeds the matrix core,
+            // with the exact lgkmcnt each step needs, and this wave's first COPIES1 copy instructions of
+            // the next tile (all of them part of its first sub-tile) issue between the matrix instructions.
+            static_assert(!WIDE || ((COPIES1 - 1) * 4 + 3 < C::N1), "the woven copies must belong to the first sub-tile");
+            static_assert(!WIDE || (COPIES1 == 9 && KEYS) || (COPIES1 == 5 && !KEYS), "one asm variant per copy count");
+            static_assert(!WIDE || IN_AGPR == (ROLE == 0 ? 32 : 24), "one asm variant per register split");
+            bf16x8 kf[LOZA_SCORE_DEPTH_576];
+            uint32_t tmp;
+            const uint32_t a_addr = smem_lds + st * C::STAGE + A_OFF + ln * A_ROW + lh * 16;
+            const uint32_t m0base = tc.dst + wave * 1024;
+            if constexpr (KEYS) {
+                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_C9_A32(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+                else LOZA_BWD_PHASE1_K32_C9_A24(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+            } else {
+                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_C5_A32(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+                else LOZA_BWD_PHASE1_K32_C5_A24(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+            }
+        } else {
 #pragma unroll
         for (int e = 0; e < 16; ++e) c[e] = 0.f;
         // (fragments of the streamed tile are fetched PF steps ahead of the matrix instruction that
@@ -396,9 +421,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // vector-memory operation in flight, the copy of the next tile included)
         {
             constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 8, EVERY = NS / COPIES1;
-            // S reads the first streamed tile; T the second when there is one (else the values are the
-            // key rows' prefix)
-            const char *ya = tile + ((ROLE == 1 && C::HAS_Y2) ? C::OFF_Y2 + ln * C::ROW2 : ln * C::ROW1) + lh * 16;
+            const char *ya = tile + A_OFF + ln * A_ROW + lh * 16;
             bf16x8 af[PF];
 #pragma unroll
             for (int d = 0; d < PF; ++d) af[d] = *(const bf16x8 *)(ya + d * 32);
@@ -409,6 +432,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 if (kk % EVERY == 0 && kk / EVERY < COPIES1 ) issue_one(tc, kk / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
         }
         // The elementwise step is shared: of this lane's four runs of four values, the S wave processes
         // runs 0, 1 and the T wave runs 2, 3; each hands the other the half of its block it does not
