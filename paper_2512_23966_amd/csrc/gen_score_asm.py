@@ -89,19 +89,54 @@ def macro_copy(dqk: int, n_copy: int, waves: int, hint: str = "") -> str:
     return text
 
 
-def macro_bwd(ks: int, n_copy: int, n_agpr: int) -> str:
-    """Phase 1 of the backward kernels: the same statement (ks k-steps, n_copy woven copies, four
-    waves), with the first n_agpr stationary fragments read from AGPRs (the rest from VGPRs): there
-    the accumulators leave part of the AGPR file free and the fragments that fit live in it."""
+def macro_bwd(ks: int, n_a: int, n_b: int, n_agpr: int, with_x: bool = True, n_voff: int = 0) -> str:
+    """Phase 1 of the backward kernels: ks k-steps against stationary fragments of which the first
+    n_agpr are read from AGPRs (the accumulators leave part of that file free) and the rest from
+    VGPRs, with ALL of this wave's copy instructions of the next streamed tile woven in: n_a into the
+    first sub-tile, n_b into the second, and one more (any sub-tile, with operands of its own) that
+    only the first nextra_ waves issue. Chunk c of a sub-tile lands 4 KB after chunk c - 1 (four waves
+    take turns)."""
     depth = min(DEPTH, ks)
+    n_copy = n_a + n_b + (1 if with_x else 0)
+    n_voff = max(n_voff, n_a + n_b + 1)       # length of the offset array; the extra instruction uses its last entry
+    t = lambda i: f"%{1 + i}"
+    tmp = f"%{depth + 1}"
+    addr = f"%{depth + 2}"
+    x = lambda kk: f"%{depth + 3 + kk}"
+    base = depth + 3 + ks
+    voff = lambda c: f"%{base + c}"
+    sg = base + n_voff                      # scalar operands: (max, src, m0) of a, of b, of the extra one; its flag
+    max_a, src_a, m0_a, max_b, src_b, m0_b, max_x, src_x, m0_x, wave, n_x = (f"%{sg + i}" for i in range(11))
+    at = {((2 * c + 1) * ks) // (2 * n_copy): c for c in range(n_copy)}
+    assert len(at) == n_copy, "at most one copy per k-step"
+    lines = ["s_waitcnt lgkmcnt(0)"]        # the waits below count this statement's own LDS reads
+    for d in range(depth):
+        lines.append(f"ds_read_b128 {t(d)}, {addr} offset:{d * 32}")
+    for kk in range(ks):
+        lines.append(f"s_waitcnt lgkmcnt({min(depth - 1, ks - 1 - kk)})")
+        lines.append(f"v_mfma_f32_32x32x16_bf16 %0, {t(kk % depth)}, {x(kk)}, {'0' if kk == 0 else '%0'}")
+        if kk + depth < ks:
+            lines.append(f"ds_read_b128 {t(kk % depth)}, {addr} offset:{(kk + depth) * 32}")
+        if kk in at:
+            c = at[kk]
+            # (the scalar add and compare write SCC: the statement names it as clobbered)
+            if c < n_a:
+                lines += [f"v_min_u32 {tmp}, {max_a}, {voff(c)}", f"s_add_u32 m0, {m0_a}, {c * 4096}", "s_nop 0",
+                          f"global_load_lds_dwordx4 {tmp}, {src_a}"]
+            elif c < n_a + n_b:
+                lines += [f"v_min_u32 {tmp}, {max_b}, {voff(c)}", f"s_add_u32 m0, {m0_b}, {(c - n_a) * 4096}", "s_nop 0",
+                          f"global_load_lds_dwordx4 {tmp}, {src_b}"]
+            else:
+                lines += [f"s_cmp_ge_u32 {wave}, {n_x}", "s_cbranch_scc1 .Lloza_nox%=", f"v_min_u32 {tmp}, {max_x}, {voff(n_voff - 1)}",
+                          f"s_mov_b32 m0, {m0_x}", "s_nop 0", f"global_load_lds_dwordx4 {tmp}, {src_x}", ".Lloza_nox%=:"]
+    lines += ["s_nop 7", "s_nop 7", "s_nop 7"]
     outs = ['"=&v"(s_)'] + [f'"=&v"(kf_[{d}])' for d in range(depth)] + ['"=&v"(tmp_)']
     ins = ['"v"(addr_)'] + [f'"{"a" if kk < n_agpr else "v"}"(xf_[{kk}])' for kk in range(ks)]
-    ins += [f'"v"(voff_[{c}])' for c in range(n_copy)] + ['"s"(max_)', '"s"(src_)', '"s"(m0base_)']
-    text = f"// backward, phase 1: {ks} k-steps, {n_copy} woven copies, fragments 0..{n_agpr - 1} in AGPRs\n"
-    text += f"#define LOZA_BWD_PHASE1_K{ks}_C{n_copy}_A{n_agpr}(s_, kf_, tmp_, addr_, xf_, voff_, max_, src_, m0base_) \\\n    asm volatile( \\\n"
-    # (the waits inside count this statement's own LDS reads: nothing else may be outstanding)
-    text += '    "s_waitcnt lgkmcnt(0)\\n" \\\n'
-    text += "".join(l.rstrip("\n") + " \\\n" for l in body_copy(ks, depth, n_copy, 4).splitlines(True))
+    ins += [f'"v"(voff_[{c}])' for c in range(n_voff)]
+    ins += [f'"s"({n})' for n in ("tc_.max1", "tc_.b1", "tc_.dst1", "tc_.max2", "tc_.b2", "tc_.dst2", "tc_.maxx", "tc_.bx", "tc_.dstx", "wave_")] + ['"n"(nextra_)']
+    text = f"// backward, phase 1: {ks} k-steps, fragments 0..{n_agpr - 1} in AGPRs, {n_a} + {n_b} + {1 if with_x else 0} woven copies\n"
+    text += f"#define LOZA_BWD_PHASE1_K{ks}_A{n_a}_B{n_b}{'' if with_x else 'N'}_G{n_agpr}(s_, kf_, tmp_, addr_, xf_, voff_, tc_, wave_, nextra_) \\\n    asm volatile( \\\n"
+    text += "".join(f'    "{l}\\n" \\\n' for l in lines)
     text += "        : " + ", ".join(outs) + " \\\n        : " + ", ".join(ins) + " \\\n        : \"memory\", \"m0\", \"scc\")\n"
     return text
 
@@ -126,6 +161,6 @@ if __name__ == "__main__":
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
     print(macro_copy(576, 4, 2, " nt"))
-    for ks, n_copy, n_agpr in ((36, 9, 32), (32, 9, 24), (36, 5, 32), (32, 5, 24)):
-        print(macro_bwd(ks, n_copy, n_agpr))
+    for ks, n_a, n_b, n_agpr in ((36, 9, 8, 32), (32, 9, 8, 24), (36, 9, 0, 32), (32, 9, 0, 24)):
+        print(macro_bwd(ks, n_a, n_b, n_agpr))
     print("#endif")

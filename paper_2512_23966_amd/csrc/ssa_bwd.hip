@@ -110,7 +110,14 @@ struct BwdCfg {
     static constexpr int N2 = HAS_Y2 ? (32 * CPR2 + 63) / 64 : 0;
     static constexpr int NSTAT = KEYS ? 1 : 0;        // + the row statistics of the tile
     static constexpr int NI = N1 + N2 + NSTAT;
-    static constexpr int PER_WAVE = (NI + 3) / 4;
+    // Who copies what: instruction c * 4 + w of a sub-tile belongs to wave w for c < A1 (A2); what is
+    // left over (at most one instruction per wave: the tails of the two sub-tiles and the statistics)
+    // is dealt one to a wave as its last, "extra" instruction. Every wave thus issues the same
+    // sequence: A1 into the first sub-tile, A2 into the second, and possibly one more.
+    static constexpr int A1 = N1 / 4, A2 = N2 / 4, R1 = N1 % 4, R2 = N2 % 4;
+    static constexpr int NEXTRA = R1 + R2 + NSTAT;
+    static_assert(NEXTRA <= 4, "one extra copy instruction per wave at most");
+    static constexpr int PER_WAVE = A1 + A2 + 1;
     static constexpr int STAGE = NI * 1024;
     static constexpr int OFF_Y2 = N1 * 1024, OFF_STAT = (N1 + N2) * 1024;
     static constexpr int PROW = 32 * 2 + 16;          // LDS bytes per row of the dS / p buffers
@@ -149,6 +156,11 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     const int G = p.G;
     const int64_t S = p.S, R = S * G;
     const int n_sink = p.n_sink, window = p.window, block = p.block;
+    // Row index -> position, once or twice per tile: a shift when the group size is a power of two
+    // (an integer division by a run-time value is dozens of dependent instructions on a wave that
+    // has nothing else to issue meanwhile).
+    const int g_log2 = (G & (G - 1)) == 0 ? __builtin_ctz((unsigned)G) : -1;
+    auto div_g = [&](int r) { return g_log2 >= 0 ? r >> g_log2 : r / G; };
 
     // ---- which work item ----------------------------------------------------------------------------
     const int n_kt = (int)((S + 63) / 64);  // key tiles of 64 keys
@@ -235,6 +247,30 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         return yt < yt_wrap ? yt : yt - nt;
     };
 
+    // KEYS: the row tiles that need no mask are a contiguous run. A tile starting at row y0 (rows
+    // y0 .. y0 + 31, positions i_lo = y0 / G .. i_hi = (y0 + 31) / G) is interior when all its rows
+    // exist, all 64 keys exist, the last key is not after the first position (j_max <= i_lo), and
+    // either all keys are sinks or the first key is inside the window of the last position
+    // (j_min >= window_begin(i_hi), which does not decrease with the position).
+    int y_int_lo = 1, y_int_hi = 0;  // (empty)
+    if (KEYS) {
+        const int64_t j_min = (int64_t)xt * 64, j_max = j_min + 63;
+        if (j_max < S) {
+            // j_max <= y0 / G  <=>  y0 >= j_max * G
+            const int64_t lo = j_max * G;
+            // rows exist: y0 + 31 < R
+            int64_t hi = R - 32;
+            if (j_max >= n_sink) {
+                // window_begin(i) <= j_min  <=>  i / block - window + 1 <= j_min / block  <=>  i <= i_w
+                const int64_t i_w = (j_min / block + window) * (int64_t)block - 1;
+                // (y0 + 31) / G <= i_w  <=>  y0 + 31 <= i_w * G + G - 1
+                const int64_t hi_w = i_w * G + G - 32;
+                if (hi_w < hi) hi = hi_w;
+            }
+            if (lo <= hi) { y_int_lo = (int)lo; y_int_hi = (int)(hi < 2147483647LL ? hi : 2147483647LL); }
+        }
+    }
+
     // From here on the two roles run separate instantiations of the same code (role 0: S = Y1 X1^T;
     // role 1: T = Y2 X2^T): each then has registers for its own operand fragments
     // and its own share of the accumulators, and no branch on the role sits inside the tile loop. The
@@ -292,56 +328,73 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         return (uint32_t)(((int64_t)(item / G) * pos_stride + item % G) * width * 2);
     };
     constexpr int W2 = (!KEYS && ALIAS) ? DQK : DV;                      // element width of a Y2 row in memory
+    // per-lane byte offset of this lane's 16 bytes within the global tile, for instruction n of a sub-tile
+    auto lane_offset = [&](int kind, int n) -> uint32_t {
+        if (kind == 3) return (lane < 15 ? lane : 15) * 16;  // 32 rows x 8 bytes of statistics
+        const int cpr = kind == 1 ? C::CPR1 : C::CPR2;
+        const int slot = n * 64 + lane, item = slot / cpr < 31 ? slot / cpr : 31;
+        const int c = slot % cpr < cpr - 2 ? slot % cpr : cpr - 2;
+        return item_offset(item, kind == 1 ? DQK : W2) + c * 16;
+    };
+    // the extra instruction of this wave (wave-uniform): 0 none, 1 / 2 instruction x_instr of the first /
+    // second sub-tile, 3 the statistics
+    int x_kind = 0, x_instr = 0;
+    if (wave < C::R1) { x_kind = 1; x_instr = 4 * C::A1 + wave; }
+    else if (wave < C::R1 + C::R2) { x_kind = 2; x_instr = 4 * C::A2 + (wave - C::R1); }
+    else if (wave < C::NEXTRA) { x_kind = 3; }
+    x_kind = __builtin_amdgcn_readfirstlane(x_kind);
+    x_instr = __builtin_amdgcn_readfirstlane(x_instr);
     uint32_t yoff[C::PER_WAVE];
 #pragma unroll
-    for (int u = 0; u < C::PER_WAVE; ++u) {
-        const int n = u * 4 + wave;
-        if (n < C::N1) {
-            const int slot = n * 64 + lane, item = slot / C::CPR1 < 31 ? slot / C::CPR1 : 31;
-            const int c = slot % C::CPR1 < C::CPR1 - 2 ? slot % C::CPR1 : C::CPR1 - 2;
-            yoff[u] = item_offset(item, DQK) + c * 16;
-        } else if (n < C::N1 + C::N2) {
-            const int slot = (n - C::N1) * 64 + lane, item = slot / C::CPR2 < 31 ? slot / C::CPR2 : 31;
-            const int c = slot % C::CPR2 < C::CPR2 - 2 ? slot % C::CPR2 : C::CPR2 - 2;
-            yoff[u] = item_offset(item, W2) + c * 16;
-        } else {
-            yoff[u] = (lane < 15 ? lane : 15) * 16;  // 32 rows x 8 bytes of statistics
-        }
-    }
+    for (int c = 0; c < C::A1; ++c) yoff[c] = lane_offset(1, c * 4 + wave);
+#pragma unroll
+    for (int c = 0; c < C::A2; ++c) yoff[C::A1 + c] = lane_offset(2, c * 4 + wave);
+    yoff[C::A1 + C::A2] = x_kind ? lane_offset(x_kind, x_instr) : 0u;
     const char *y1_all = KEYS ? (const char *)p.q : (const char *)p.k;
     const char *y2_all = KEYS ? (const char *)p.dout : (const char *)p.v;
     // what the copy instructions of one tile share (all wave-uniform)
     struct TileCopy {
-        const char *b1, *b2, *b3;
-        uint32_t max1, max2, dst;
+        const char *b1, *b2, *bx;         // global start of the tile's sub-tiles; of the extra instruction's
+        uint32_t max1, max2, maxx;        // largest valid per-lane offset
+        uint32_t dst1, dst2, dstx;        // LDS address of this wave's first chunk of a sub-tile; of its extra chunk
     };
+    // (everything about a tile that does not depend on the tile is worked out here, once: the wave has
+    // nothing else to issue while it computes addresses, so every instruction of the per-tile part
+    // costs its full latency)
+    const int n_y = (int)(KEYS ? R : S);                              // items on the streamed side (fits 32 bits)
+    const int64_t row_base = KEYS ? (int64_t)b * S * p.Hq + (int64_t)g * G : (int64_t)b * S * p.Hkv + g;
+    const int row_step = KEYS ? p.Hq - G : 0;                         // KEYS: tensor rows skipped per position
+    const char *stat_base = (const char *)(p.rowstat + ((int64_t)b * p.Hkv + g) * p.r_pad);
+    const uint32_t max1_full = item_offset(31, DQK) + (C::CPR1 - 2) * 16;
+    const uint32_t max2_full = item_offset(31, W2) + (C::CPR2 - 2) * 16;
+    const uint32_t dstx_off = (x_kind == 1 ? x_instr : x_kind == 2 ? C::N1 + x_instr : C::N1 + C::N2) * 1024;
     auto plan_tile = [&](int t, int stage) {
-        const int64_t y0 = (int64_t)y_tile(t) * 32;                  // first row / key of the tile
-        const int64_t y_left = (KEYS ? R : S) - 1 - y0;
-        const int lim = y_left < 31 ? (int)y_left : 31;              // last valid item of the tile
-        int64_t row0;                                                // tensor row (of d elements) the tile starts at
-        if (KEYS) {
-            const int64_t i0 = y0 / G;
-            const int hh0 = (int)(y0 - i0 * G);
-            row0 = ((int64_t)b * S + i0) * p.Hq + (int64_t)g * G + hh0;
-        } else {
-            row0 = ((int64_t)b * S + y0) * p.Hkv + g;
-        }
+        const int y0 = y_tile(t) * 32;                               // first row / key of the tile
+        // tensor row (of d elements) the tile starts at
+        const int64_t row0 = KEYS ? row_base + y0 + (int64_t)div_g(y0) * row_step : row_base + (int64_t)y0 * p.Hkv;
         TileCopy tc;
-        tc.b1 = y1_all + row0 * DQK * 2;
-        tc.b2 = y2_all + row0 * W2 * 2;
-        tc.b3 = (const char *)(p.rowstat + ((int64_t)b * p.Hkv + g) * p.r_pad + y0);
-        tc.max1 = item_offset(lim, DQK) + (C::CPR1 - 2) * 16;
-        tc.max2 = item_offset(lim, W2) + (C::CPR2 - 2) * 16;
-        tc.dst = smem_lds + stage * C::STAGE;
+        tc.b1 = y1_all + row0 * (DQK * 2);
+        tc.b2 = y2_all + row0 * (W2 * 2);
+        tc.max1 = max1_full;
+        tc.max2 = max2_full;
+        if (y0 + 31 >= n_y) {                                        // the ragged last tile: cut at its last valid item
+            const int lim = n_y - 1 - y0;
+            tc.max1 = item_offset(lim, DQK) + (C::CPR1 - 2) * 16;
+            tc.max2 = item_offset(lim, W2) + (C::CPR2 - 2) * 16;
+        }
+        const uint32_t base = smem_lds + stage * C::STAGE;
+        tc.dst1 = base + wave * 1024;
+        tc.dst2 = base + C::OFF_Y2 + wave * 1024;
+        tc.bx = x_kind == 1 ? tc.b1 : x_kind == 2 ? tc.b2 : stat_base + (int64_t)y0 * 8;
+        tc.maxx = x_kind == 1 ? tc.max1 : x_kind == 2 ? tc.max2 : 0xffffffffu;
+        tc.dstx = base + dstx_off;
         return tc;
     };
-    // copy instruction u of this wave (u < PER_WAVE, a constant after unrolling)
-    auto issue_one = [&](const TileCopy &tc, int u) {
-        const int n = u * 4 + wave;  // wave-uniform
-        if (n < C::N1) copy_1k(tc.b1, yoff[u] < tc.max1 ? yoff[u] : tc.max1, tc.dst + n * 1024);
-        else if (n < C::N1 + C::N2) copy_1k(tc.b2, yoff[u] < tc.max2 ? yoff[u] : tc.max2, tc.dst + n * 1024);
-        else if (n < C::NI) copy_1k(tc.b3, yoff[u], tc.dst + n * 1024);
+    // copy instruction c of this wave (c < PER_WAVE, a constant after unrolling)
+    auto issue_one = [&](const TileCopy &tc, int c) {
+        if (c < C::A1) copy_1k(tc.b1, yoff[c] < tc.max1 ? yoff[c] : tc.max1, tc.dst1 + c * 4096);
+        else if (c < C::A1 + C::A2) copy_1k(tc.b2, yoff[c] < tc.max2 ? yoff[c] : tc.max2, tc.dst2 + (c - C::A1) * 4096);
+        else if (x_kind) copy_1k(tc.bx, yoff[c] < tc.maxx ? yoff[c] : tc.maxx, tc.dstx);  // wave-uniform
     };
 
     constexpr int ND = ROLE == 0 ? C::ND0 : C::ND1;  // column blocks of this wave (each for both blocks of X)
@@ -365,7 +418,6 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
 
     char *region = smem + C::OFF_BUF + xb * C::XREGION;   // dS rows of this block of X, then its p rows
     char *xch = smem + C::OFF_XCH + xb * C::XCH;          // T of this block of X, from its role-1 wave to its role-0 wave
-    const int j_min_x = xt * 64, j_max_x = xt * 64 + 63;   // KEYS: the keys of this workgroup
 
     {
         const TileCopy tc0 = plan_tile(0, 0);
@@ -376,10 +428,10 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     // for here, with a wait the compiler sees: left to its own bookkeeping it would wait for those
     // loads inside the loop, with counts that also drain the tile copies it does not know about.
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    // The copy instructions of the next tile are issued a few at a time between the matrix
-    // instructions of both phases: issued in one burst they fill the memory pipeline's queue and the
-    // wave stalls on them for longer than a phase takes (measured).
-    constexpr int COPIES1 = (C::PER_WAVE + 1) / 2, COPIES2 = C::PER_WAVE - COPIES1;
+    // The copy instructions of the next tile are issued one at a time between the matrix instructions
+    // of phase 1 (in one burst they fill the memory pipeline's queue and the wave stalls on them for
+    // longer than a phase takes), and none in phase 2: a copy requested that late is still on its way
+    // when the next iteration waits for it (measured: 680 cycles per tile).
     for (int u = 0; u < nt; ++u) {
         const int st = u & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
@@ -396,21 +448,19 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         if constexpr (WIDE) {
             // Wide rows: the whole phase is one generated asm statement (score_asm.h), as the forward's
             // score phase is: fragment kk + 6 is fetched from LDS while fragment kk feeds the matrix core,
-            // with the exact lgkmcnt each step needs, and this wave's first COPIES1 copy instructions of
-            // the next tile (all of them part of its first sub-tile) issue between the matrix instructions.
-            static_assert(!WIDE || ((COPIES1 - 1) * 4 + 3 < C::N1), "the woven copies must belong to the first sub-tile");
-            static_assert(!WIDE || (COPIES1 == 9 && KEYS) || (COPIES1 == 5 && !KEYS), "one asm variant per copy count");
+            // with the exact lgkmcnt each step needs, and this wave's copy instructions of the next tile
+            // issue between the matrix instructions.
+            static_assert(!WIDE || (C::A1 == 9 && C::A2 == (KEYS ? 8 : 0)), "one asm variant per copy plan");
             static_assert(!WIDE || IN_AGPR == (ROLE == 0 ? 32 : 24), "one asm variant per register split");
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
             uint32_t tmp;
             const uint32_t a_addr = smem_lds + st * C::STAGE + A_OFF + ln * A_ROW + lh * 16;
-            const uint32_t m0base = tc.dst + wave * 1024;
             if constexpr (KEYS) {
-                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_C9_A32(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
-                else LOZA_BWD_PHASE1_K32_C9_A24(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_A9_B8_G32(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
+                else LOZA_BWD_PHASE1_K32_A9_B8_G24(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
             } else {
-                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_C5_A32(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
-                else LOZA_BWD_PHASE1_K32_C5_A24(c, kf, tmp, a_addr, xf, yoff, tc.max1, tc.b1, m0base);
+                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_A9_B0_G32(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
+                else LOZA_BWD_PHASE1_K32_A9_B0_G24(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
             }
         } else {
 #pragma unroll
@@ -420,7 +470,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         // which costs registers it then finds by spilling -- and a reload from scratch waits for every
         // vector-memory operation in flight, the copy of the next tile included)
         {
-            constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 8, EVERY = NS / COPIES1;
+            constexpr int NS = ROLE == 0 ? DQK / 16 : DV / 16, PF = 8, EVERY = NS / C::PER_WAVE > 0 ? NS / C::PER_WAVE : 1;
             const char *ya = tile + A_OFF + ln * A_ROW + lh * 16;
             bf16x8 af[PF];
 #pragma unroll
@@ -429,9 +479,12 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             for (int kk = 0; kk < NS; ++kk) {
                 c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk % PF], xf[kk], c, 0, 0, 0);
                 if (kk + PF < NS) af[kk % PF] = *(const bf16x8 *)(ya + (kk + PF) * 32);
-                if (kk % EVERY == 0 && kk / EVERY < COPIES1 ) issue_one(tc, kk / EVERY);
+                if (kk % EVERY == 0 && kk / EVERY < C::PER_WAVE) issue_one(tc, kk / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            // (copies that did not find a slot above)
+#pragma unroll
+            for (int cu = (NS + EVERY - 1) / EVERY; cu < C::PER_WAVE; ++cu) issue_one(tc, cu);
         }
         }
         // The elementwise step is shared: of this lane's four runs of four values, the S wave processes
@@ -459,23 +512,35 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 // lane = query row, values = keys y0 + 8 qd + 4 lh + t
                 interior = (y0 + 31 <= i_min) && ((y0 + 31 < n_sink) || (y0 >= w_lo_max));
             } else {
-                // lane = key, values = query rows y0 + 8 qd + 4 lh + t (row counts fit 32 bits)
-                const int i_lo = y0 / G, i_hi = (y0 + 31) / G;
-                interior = ((int64_t)y0 + 31 < R) && (j_max_x < S) && (j_max_x <= i_lo) &&
-                           ((j_max_x < n_sink) || (j_min_x >= window_begin_of(i_hi, window, block)));
+                // lane = key, values = query rows y0 + 8 qd + 4 lh + t
+                interior = y0 >= y_int_lo && y0 <= y_int_hi;
             }
             // KEYS: position of row y0 + y is i_tile + (y >> g_shift): a tile is 32 / G whole positions
             // (G a power of two) or part of one position (G a multiple of 32: the shift drops every y)
-            const int i_tile = KEYS ? y0 / G : 0;
-            const int w_lo_tile = KEYS ? window_begin_of(i_tile, window, block) : 0;
             // (one branch for the whole tile: interior tiles, nearly all of them, evaluate no predicate)
             auto elementwise = [&](auto masked) {
             constexpr bool MASKED = decltype(masked)::value;
+            int i_tile = 0, w_lo_tile = 0;
+            if constexpr (MASKED && KEYS) {
+                i_tile = div_g(y0);
+                w_lo_tile = window_begin_of(i_tile, window, block);
+            }
+            // (everything this step reads from LDS is requested before the first result is written back:
+            // a read behind a write would wait for it, and the wave has nothing to hide that behind)
+            float4 o4[2];
+            float2 sd[2][4];
+#pragma unroll
+            for (int q2 = 0; q2 < 2; ++q2) {
+                o4[q2] = *(const float4 *)(xch + (((1 - ROLE) * 2 + q2) * 64 + lane) * 16);
+                if (KEYS) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) sd[q2][t] = stat[8 * (QD_OWN + q2) + 4 * lh + t];
+                }
+            }
 #pragma unroll
             for (int q2 = 0; q2 < 2; ++q2) {
                 const int qd = QD_OWN + q2;
-                const float4 o4 = *(const float4 *)(xch + (((1 - ROLE) * 2 + q2) * 64 + lane) * 16);
-                const float other[4] = {o4.x, o4.y, o4.z, o4.w};   // the other wave's block: T for the S wave, S for the T wave
+                const float other[4] = {o4[q2].x, o4[q2].y, o4[q2].z, o4[q2].w};   // the other wave's block: T for the S wave, S for the T wave
                 float pv[4], dsv[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -487,8 +552,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                         const int j = y0 + y;
                         if (MASKED) ok = (j <= x_i) & ((j < n_sink) | (j >= w_lo_row));
                     } else {
-                        const float2 sd = stat[y];
-                        lse2 = sd.x; D = sd.y;
+                        lse2 = sd[q2][t].x; D = sd[q2][t].y;
                         if (MASKED) {
                             const int i = i_tile + (y >> g_shift), j = (int)x_idx;
                             const int w_lo = G >= 32 ? w_lo_tile : window_begin_of(i, window, block);
@@ -524,7 +588,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             // (Y2^T p, the dV part of a shared accumulator) exists for the first NDBL blocks. Fetched PF
             // entries ahead; every fragment feeds one matrix instruction per block of X.
             constexpr int PER_KS = ND + NDBL;
-            constexpr int NF = 2 * PER_KS, PF = 4, EVERY = COPIES2 > 0 ? (NF / COPIES2 > 0 ? NF / COPIES2 : 1) : NF;
+            constexpr int NF = 2 * PER_KS, PF = 4;
             auto entry = [](int m, int &ks, int &a, int &prod) {
                 ks = m / PER_KS;
                 const int r = m % PER_KS;
@@ -558,13 +622,8 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 acc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, use_p ? b_p[1] : b_ds[1], acc[a][1], 0, 0, 0);
                 if (m + PF < NF) fr[m % PF] = frag(m + PF);
                 if (m == PER_KS - 1) load_b(1);  // the second key step's dS and p
-                if (m % EVERY == 0 && m / EVERY < COPIES2 ) issue_one(tc, COPIES1 + m / EVERY);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // (copies that did not find a slot above)
-#pragma unroll
-            for (int cu = (NF + EVERY - 1) / EVERY; cu < COPIES2; ++cu)
-                issue_one(tc, COPIES1 + cu);
         }
     }
 
