@@ -277,16 +277,20 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         const char *ksrc, *vsrc;
         uint32_t kdst, vdst, kmax, vmax;
     };
+    // byte offset of cache row `row` (a row index fits 32 bits unless the cache is paged)
+    auto tile_bytes = [&](int64_t row, uint32_t stride) -> int64_t {
+        return paged ? row * (int64_t)stride : (int64_t)((uint64_t)(uint32_t)row * stride);
+    };
     auto plan_copy = [&](int t, int stage, int64_t row) {
-        const int64_t j0 = (int64_t)key_tile(t) * N;
         // rows of the tile at or past the sequence end fetch from its last valid row instead:
         // they are dead (j > i) and only have to be finite
-        const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
+        const int left = (int)L - 1 - key_tile(t) * N;
+        const uint32_t lim = left < N - 1 ? (uint32_t)left : (uint32_t)(N - 1);
         TileCopy tc;
-        tc.ksrc = kbase + row * (int64_t)pos_stride_k;
+        tc.ksrc = kbase + tile_bytes(row, pos_stride_k);
         tc.kdst = smem_lds + stage * C::STAGE + (k_first + cw) * 1024;
         tc.kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
-        tc.vsrc = vbase + row * (int64_t)pos_stride_v;
+        tc.vsrc = vbase + tile_bytes(row, pos_stride_v);
         tc.vdst = smem_lds + stage * C::STAGE + C::KTILE + cw * 1024;
         tc.vmax = lim * pos_stride_v + (C::VCPR - 2) * 16;
         return tc;
@@ -341,9 +345,10 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     auto score_tile_copy = [&](int stage, f32x16 &s, int t_copy, int stage_copy, int64_t row_copy) {
         if constexpr (WEAVE) {
             const uint32_t kaddr = smem_lds + stage * C::STAGE + ln * C::KROW + lh * 16;
-            const int64_t j0 = (int64_t)key_tile(t_copy) * N;
-            const uint32_t lim = (L - 1 - j0) < (N - 1) ? (uint32_t)(L - 1 - j0) : (uint32_t)(N - 1);
-            const char *ksrc = kbase + row_copy * (int64_t)pos_stride_k;
+            // (scalar arithmetic the wave has nothing to overlap with: 32-bit where the values allow)
+            const int left = (int)L - 1 - key_tile(t_copy) * N;  // rows of the tile after its first that exist
+            const uint32_t lim = left < N - 1 ? (uint32_t)left : (uint32_t)(N - 1);
+            const char *ksrc = kbase + tile_bytes(row_copy, pos_stride_k);
             const uint32_t kmax = lim * pos_stride_k + (C::KCPR - 2) * 16;
             const uint32_t m0base = smem_lds + stage_copy * C::STAGE + wave * 1024;
             static_assert(!WEAVE || DECODE || (LOZA_SCORE_COPIES_576_W4 * NW <= C::K_INSTR && C::K_PER_WAVE <= LOZA_SCORE_COPIES_576_W4 + 1), "copy plan");
