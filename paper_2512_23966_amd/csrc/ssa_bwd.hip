@@ -30,7 +30,8 @@
 //               transposed from LDS (ds_read_b64_tr_b16) as the forward's value phase does, and
 //               every fragment read feeds two matrix instructions.
 // The streamed tiles travel global -> LDS with global_load_lds_dwordx4 into a ring of two stages,
-// the copy instructions of the next tile issued between the matrix instructions of both phases.
+// the copy instructions of the next tile issued between the matrix instructions of phase 1 (a copy
+// requested later than that is still on its way when the next iteration needs it).
 // After the setup the two roles run separate instantiations of the tile loop.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
