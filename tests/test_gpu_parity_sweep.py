@@ -1,0 +1,95 @@
+"""Seeded random sweep of pattern parameters: prefill, decode and backward against the oracle.
+
+The hand-picked cases of the other files name the edges one at a time; here the edges meet at random:
+a gap between the sink tiles and the window tiles (or none), windows shorter and longer than a tile,
+block-granular patterns whose blocks straddle tiles, ragged sequence ends, sink counts beyond the
+sequence. Every case is derived from its index alone, so a failure names a reproducible case."""
+import numpy as np
+import pytest
+import torch
+
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(shape, seed, device):
+    g = torch.Generator(device=device).manual_seed(seed)
+    return torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+
+
+def _pattern(case: int):
+    """(S, n_sink, window, block) of sweep case `case`; block None = token-granular."""
+    r = np.random.default_rng(1000 + case)
+    S = int(r.integers(1, 420))
+    block = [None, None, 8, 32, 48][int(r.integers(0, 5))]
+    if block is None:
+        ns = int(r.choice([0, 1, int(r.integers(0, 80)), int(r.integers(0, S + 40))]))
+        win = int(r.choice([1, int(r.integers(1, 40)), int(r.integers(1, 200))]))
+    else:
+        ns = int(r.integers(0, 3))
+        win = int(r.integers(1, 5))
+    return S, ns, win, block
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_mla_prefill_sweep(gpu_device, case):
+    S, ns, win, block = _pattern(case)
+    B = 1 + case % 2
+    q = _rand((B, S, 64, 576), 7000 + case, gpu_device)
+    k = _rand((B, S, 1, 576), 8000 + case, gpu_device)
+    scale = 192 ** -0.5
+    out, lse = H.run_prefill(q, k, k, ns, win, scale, d_v=512, block=block)
+    rb, rh, ri = H.all_rows(B, 64, S)
+    H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, f"sweep {case}: B{B} S{S} ns{ns} W{win} b{block}", block=block)
+
+
+@pytest.mark.parametrize("case", range(100, 116))
+def test_d128_prefill_sweep(gpu_device, case):
+    S, ns, win, block = _pattern(case)
+    Hq, Hkv = [(4, 4), (8, 2), (2, 1), (6, 3)][case % 4]
+    q = _rand((1, S, Hq, 128), 7000 + case, gpu_device)
+    k = _rand((1, S, Hkv, 128), 8000 + case, gpu_device)
+    v = _rand((1, S, Hkv, 128), 9000 + case, gpu_device)
+    scale = 128 ** -0.5
+    out, lse = H.run_prefill(q, k, v, ns, win, scale, block=block)
+    rb, rh, ri = H.all_rows(1, Hq, S)
+    H.compare_prefill(q, k, v, out, lse, rb, rh, ri, ns, win, scale, f"sweep {case}: Hq{Hq}/{Hkv} S{S} ns{ns} W{win} b{block}", block=block)
+
+
+@pytest.mark.parametrize("case", range(200, 216))
+def test_mla_decode_sweep(gpu_device, case):
+    S_max, ns, win, block = _pattern(case)
+    S_max += 200  # long enough for the split kernel on most sequences
+    r = np.random.default_rng(2000 + case)
+    B = 3
+    lens = [int(x) for x in r.integers(1, S_max + 1, size=B)]
+    lens[0] = S_max
+    q = _rand((B, 64, 576), 7000 + case, gpu_device)
+    kc = _rand((B, S_max, 1, 576), 8000 + case, gpu_device)
+    seqlens = torch.tensor(lens, dtype=torch.int32, device=gpu_device)
+    scale = 192 ** -0.5
+    out, lse = H.run_decode(q, kc, kc, seqlens, ns, win, scale, d_v=512, block=block)
+    rb = np.repeat(np.arange(B), 64)
+    rh = np.tile(np.arange(64), B)
+    H.compare_decode(q, kc, kc, seqlens, out, lse, rb, rh, ns, win, scale, f"sweep {case}: lens{lens} ns{ns} W{win} b{block}", block=block)
+
+
+@pytest.mark.parametrize("case", range(300, 324))
+def test_backward_sweep(gpu_device, case):
+    S, ns, win, block = _pattern(case)
+    S = min(S, 260)
+    mla = case % 2 == 0
+    if mla:
+        Hq, Hkv, d_qk, d_v, alias, scale = 64, 1, 576, 512, True, 192 ** -0.5
+    else:
+        Hq, Hkv = [(4, 4), (8, 2), (32, 1)][(case // 2) % 3]
+        d_qk, d_v, alias, scale = 128, 128, case % 4 == 1, 128 ** -0.5
+    q = _rand((1, S, Hq, d_qk), 7000 + case, gpu_device)
+    k = _rand((1, S, Hkv, d_qk), 8000 + case, gpu_device)
+    v = k if alias else _rand((1, S, Hkv, d_v), 9000 + case, gpu_device)
+    dout = _rand((1, S, Hq, d_v), 9500 + case, gpu_device)
+    out, lse = H.oracle_forward_all(q, k, v, ns, win, scale, d_v, block)
+    got = H.run_backward(q, k, v, out, lse, dout, ns, win, scale, block)
+    H.compare_backward(q, k, v, out, lse, dout, got, ns, win, scale,
+                       f"sweep {case}: Hq{Hq}/{Hkv} d{d_qk} alias{alias} S{S} ns{ns} W{win} b{block}", block)
