@@ -433,15 +433,12 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     // of phase 1 (in one burst they fill the memory pipeline's queue and the wave stalls on them for
     // longer than a phase takes), and none in phase 2: a copy requested that late is still on its way
     // when the next iteration waits for it (measured: 680 cycles per tile).
-    for (int u = 0; u < nt; ++u) {
-        const int st = u & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
-        __syncthreads();                                  // ... everyone's; tile u - 1 is no longer read
-        const TileCopy tc = plan_tile(u + 1 < nt ? u + 1 : u, st ^ 1);
+    constexpr int QD_OWN = ROLE == 0 ? 0 : 2, QD_GIVE = ROLE == 0 ? 2 : 0;
+    // The four steps of a tile, as the two schedules below string them together.
+    // Phase 1 on the tile in stage `st`, with this wave's copy instructions of plan `tc` woven in:
+    auto phase1 = [&](const int st, const TileCopy &tc, f32x16 &c) {
         const char *tile = smem + st * C::STAGE;
-
         // ---- phase 1: one 32 x 32 block of S or T ---------------------------------------------------
-        f32x16 c;
         // S reads the first streamed tile; T the second when there is one (else the values are the key
         // rows' prefix)
         constexpr int A_OFF = (ROLE == 1 && C::HAS_Y2) ? C::OFF_Y2 : 0, A_ROW = (ROLE == 1 && C::HAS_Y2) ? C::ROW2 : C::ROW1;
@@ -488,10 +485,11 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             for (int cu = (NS + EVERY - 1) / EVERY; cu < C::PER_WAVE; ++cu) issue_one(tc, cu);
         }
         }
+    };
+    auto hand_over = [&](const f32x16 &c) {
         // The elementwise step is shared: of this lane's four runs of four values, the S wave processes
         // runs 0, 1 and the T wave runs 2, 3; each hands the other the half of its block it does not
         // process itself (xch: [role of the writer][run][lane] x 16 bytes).
-        constexpr int QD_OWN = ROLE == 0 ? 0 : 2, QD_GIVE = ROLE == 0 ? 2 : 0;
 #pragma unroll
         for (int q2 = 0; q2 < 2; ++q2) {
             const int qd = QD_GIVE + q2;
@@ -499,13 +497,15 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             w.x = c[4 * qd]; w.y = c[4 * qd + 1]; w.z = c[4 * qd + 2]; w.w = c[4 * qd + 3];
             *(float4 *)(xch + ((ROLE * 2 + q2) * 64 + lane) * 16) = w;
         }
-        __syncthreads();
-
+    };
+    // (tile `t_idx` of this work item, in stage `st`)
+    auto elementwise_step = [&](const f32x16 &c, const int t_idx, const int st) {
+        const char *tile = smem + st * C::STAGE;
         // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
         // four values at a time: this lane's 16 values are four runs of four consecutive y, and a run
         // is one 8-byte store into the [x][y] buffers (y contiguous)
         {
-            const int y0 = y_tile(u) * 32;
+            const int y0 = y_tile(t_idx) * 32;
             char *ps = region + ln * C::PROW + (4 * lh) * 2;
             const float2 *stat = (const float2 *)(tile + C::OFF_STAT);
             bool interior;
@@ -579,8 +579,9 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             if (interior) elementwise(std::false_type{});
             else elementwise(std::true_type{});
         }
-        __syncthreads();
-
+    };
+    auto phase2 = [&](const int st) {
+        const char *tile = smem + st * C::STAGE;
         // ---- phase 2: Acc^T[column block][x] += Y^T dS (+ Y2^T p), both blocks of X per fragment -------
         {
             const char *b0 = smem + C::OFF_BUF + ln * C::PROW + lh * 16;   // dS rows of block 0 of X ([x][y])
@@ -626,6 +627,23 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+    };
+
+    // Two stages, three barriers per tile: (A) tile u has landed and tile u - 1 is no longer read,
+    // (B) the halves of S and T are handed over, (C) dS and p are complete. (A third stage fits the dQ
+    // kernel and lets phase 2 of a tile follow phase 1 of the next without barrier A: built, 0.4 %.)
+    for (int u = 0; u < nt; ++u) {
+        const int st = u & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of tile u have landed ...
+        __syncthreads();                                  // ... everyone's; tile u - 1 is no longer read
+        const TileCopy tc = plan_tile(u + 1 < nt ? u + 1 : u, st ^ 1);
+        f32x16 c;
+        phase1(st, tc, c);
+        hand_over(c);
+        __syncthreads();
+        elementwise_step(c, u, st);
+        __syncthreads();
+        phase2(st);
     }
 
     // (the last iteration copied its own tile once more rather than branch around every copy
