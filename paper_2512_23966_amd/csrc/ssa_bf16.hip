@@ -431,45 +431,47 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     // wavefront half + scale, 3 reference update, then per pair of scores i: 4+3i and 5+3i one
     // exponential each, 6+3i bf16 pack + running sums; last the hand-over through LDS. The empty asm
     // statements anchor each job's results in its slot (the optimiser otherwise sinks all of this
-    // arithmetic below the last matrix instruction).
+    // arithmetic below the last matrix instruction); where the softmax runs on its own (the decode's
+    // scoring waves) there are none, and the sixteen independent chains overlap as the scheduler likes.
     constexpr int SM_JOBS = 4 + 3 * 8 + 1;
-    auto sm_job = [&](const int j, f32x16 &s, const int j0, const float lazy, const int pbuf) {
+    auto sm_job = [&](auto anchored, const int j, f32x16 &s, const int j0, const float lazy, const int pbuf) {
+        constexpr bool ANCHOR = decltype(anchored)::value;
         const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
         if (j == 0) {
             sm_mask(s, j0);
             sm_mx = sm_max8(s, 0);
-            asm volatile("" : "+v"(s), "+v"(sm_mx));
+            if constexpr (ANCHOR) asm volatile("" : "+v"(s), "+v"(sm_mx));
         } else if (j == 1) {
             sm_mx = fmaxf(sm_mx, sm_max8(s, 8));
-            asm volatile("" : "+v"(sm_mx));
+            if constexpr (ANCHOR) asm volatile("" : "+v"(sm_mx));
         } else if (j == 2) {
             sm_mx = max_with_other_half(sm_mx) * p.scale_log2;  // scale > 0: maximum of the scaled scores
-            asm volatile("" : "+v"(sm_mx));
+            if constexpr (ANCHOR) asm volatile("" : "+v"(sm_mx));
         } else if (j == 3) {
             sm_decide(sm_mx, lazy);
-            asm volatile("" : "+v"(sm_alpha), "+v"(sm_m_use), "+v"(m_ref));
+            if constexpr (ANCHOR) asm volatile("" : "+v"(sm_alpha), "+v"(sm_m_use), "+v"(m_ref));
         } else if (j < SM_JOBS - 1) {
             const int i = (j - 4) / 3, part = (j - 4) % 3, e = 2 * i;
             if (part == 0) {
                 // exp2(scale*log2(e)*s - m): a dead key (s = -inf) gives exactly 0
                 s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], p.scale_log2, -sm_m_use));
-                asm volatile("" : "+v"(s));
+                if constexpr (ANCHOR) asm volatile("" : "+v"(s));
             } else if (part == 1) {
                 s[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], p.scale_log2, -sm_m_use));
-                asm volatile("" : "+v"(s));
+                if constexpr (ANCHOR) asm volatile("" : "+v"(s));
             } else {
                 sm_pk[i] = pack_bf16(s[e], s[e + 1]);
                 if (PRECISE) {
                     // second bf16 term of each weight: what the first rounding lost
                     const float h0 = __builtin_bit_cast(float, sm_pk[i] << 16), h1 = __builtin_bit_cast(float, sm_pk[i] & 0xffff0000u);
                     sm_pk_lo[i] = pack_bf16(s[e] - h0, s[e + 1] - h1);
-                    asm volatile("" : "+v"(sm_pk_lo[i]));
+                    if constexpr (ANCHOR) asm volatile("" : "+v"(sm_pk_lo[i]));
                 }
                 sm_psum += s[e] + s[e + 1];
                 // the sum of the two rounded values, by one dot product with (1, 1)
                 sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk[i]), ones, sm_rsum, false);
                 if (PRECISE) sm_rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, sm_pk_lo[i]), ones, sm_rsum, false);
-                asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum), "+v"(sm_pk[i]));
+                if constexpr (ANCHOR) asm volatile("" : "+v"(sm_psum), "+v"(sm_rsum), "+v"(sm_pk[i]));
             }
         } else if (j == SM_JOBS - 1) {
             sm_end_fn(pbuf);
@@ -477,7 +479,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     };
     auto softmax_tile = [&](f32x16 &s, const int j0, const int pbuf, const float lazy) {
 #pragma unroll
-        for (int j = 0; j < SM_JOBS; ++j) sm_job(j, s, j0, lazy, pbuf);
+        for (int j = 0; j < SM_JOBS; ++j) sm_job(std::false_type{}, j, s, j0, lazy, pbuf);
     };
 
     // ---- accumulator rescale of one tile (rare after the first tiles) -----------------------------------
@@ -573,7 +575,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
                 if (WITH_SOFTMAX) {
 #pragma unroll
                     for (int jj = 0; jj < JPS; ++jj)
-                        if (slot * JPS + jj < SM_JOBS) sm_job(slot * JPS + jj, s, j0_next, lazy, pbuf_next);
+                        if (slot * JPS + jj < SM_JOBS) sm_job(std::true_type{}, slot * JPS + jj, s, j0_next, lazy, pbuf_next);
                 }
                 after_slot(slot, NSLOT);
                 __builtin_amdgcn_sched_barrier(0);
