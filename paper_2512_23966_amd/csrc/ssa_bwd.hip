@@ -434,7 +434,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
     // longer than a phase takes), and none in phase 2: a copy requested that late is still on its way
     // when the next iteration waits for it (measured: 680 cycles per tile).
     constexpr int QD_OWN = ROLE == 0 ? 0 : 2, QD_GIVE = ROLE == 0 ? 2 : 0;
-    // The four steps of a tile, as the two schedules below string them together.
+    // The four steps of a tile, strung together by the tile loop below.
     // Phase 1 on the tile in stage `st`, with this wave's copy instructions of plan `tc` woven in:
     auto phase1 = [&](const int st, const TileCopy &tc, f32x16 &c) {
         const char *tile = smem + st * C::STAGE;
