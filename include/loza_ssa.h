@@ -272,6 +272,23 @@ int loza_ssa_backward_blocks(const void *q, const void *k, const void *v, const 
                              int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * fp32 twins of loza_ssa_backward and loza_ssa_backward_blocks (the gradient of the paper's Eq. 4, as
+ * above): fp32 in, fp32 arithmetic, fp32 out, the layouts of the bf16 calls with float elements; out
+ * and lse are what loza_ssa_prefill_f32 returned. Any d_qk, d_v in [1, 256], any Hq / Hkv; v may alias
+ * k with d_v <= d_qk (dk then receives the whole gradient of the shared tensor and dv is ignored);
+ * scale finite, any sign. No workspace; deterministic (every sum runs in a fixed order). Plain vector
+ * arithmetic (no matrix cores): the small-shape check of the method, not a fast path.
+ */
+int loza_ssa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *lse,
+                          const float *dout, float *dq, float *dk, float *dv,
+                          int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale, void *stream);
+int loza_ssa_backward_blocks_f32(const float *q, const float *k, const float *v, const float *out, const float *lse,
+                                 const float *dout, float *dq, float *dk, float *dv,
+                                 int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
 /* Host-only. Workspace bytes of loza_ssa_backward / loza_ssa_backward_blocks for these sizes
  * (v_aliases_k: nonzero when v == k will be passed); 0 on sizes the call would reject. */
 size_t loza_ssa_backward_workspace_bytes(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,

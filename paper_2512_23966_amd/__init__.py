@@ -15,4 +15,5 @@ from .binding import (  # noqa: F401
     loza_ssa_extend, loza_ssa_extend_blocks, loza_ssa_extend_paged, loza_ssa_extend_paged_blocks,
     loza_ssa_backward, loza_ssa_backward_blocks,
     loza_ssa_backward_workspace_bytes, loza_ssa_backward_workspace_bytes_blocks,
+    loza_ssa_backward_f32, loza_ssa_backward_blocks_f32,
 )

@@ -31,6 +31,7 @@ EXPORTS = (
     "loza_ssa_extend", "loza_ssa_extend_blocks", "loza_ssa_extend_paged", "loza_ssa_extend_paged_blocks",
     "loza_ssa_backward", "loza_ssa_backward_blocks",
     "loza_ssa_backward_workspace_bytes", "loza_ssa_backward_workspace_bytes_blocks",
+    "loza_ssa_backward_f32", "loza_ssa_backward_blocks_f32",
 )
 
 
@@ -94,6 +95,10 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_backward.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
         L.loza_ssa_backward_blocks.restype = ci
         L.loza_ssa_backward_blocks.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_backward_f32.restype = ci
+        L.loza_ssa_backward_f32.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_backward_blocks_f32.restype = ci
+        L.loza_ssa_backward_blocks_f32.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp]
         L.loza_ssa_backward_workspace_bytes.restype = sz
         L.loza_ssa_backward_workspace_bytes.argtypes = [ci, ci, ci, i64, ci, ci, i64, i64, ci]
         L.loza_ssa_backward_workspace_bytes_blocks.restype = sz
@@ -412,6 +417,40 @@ def _backward_common(fn_name, q, k, v, out, lse, dout, dq, dk, dv, pattern, scal
                                  _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != LOZA_OK:
         raise LozaError(rc, fn_name)
+
+
+def _backward_f32_common(fn_name, q, k, v, out, lse, dout, dq, dk, dv, pattern, scale, stream):
+    """fp32 SSA backward: the tensors of :func:`_backward_common` with float32 elements, no workspace."""
+    B, S, Hq, d_qk = q.shape
+    Hkv = k.shape[2]
+    d_v = out.shape[3]
+    if k.shape != (B, S, Hkv, d_qk) or out.shape != (B, S, Hq, d_v) or dout.shape != out.shape \
+            or lse.shape != (B, Hq, S) or dq.shape != q.shape or dk.shape != k.shape:
+        raise ValueError("shape mismatch between q, k, out, lse, dout, dq, dk")
+    f32 = torch.float32
+    kp = _dev_ptr(k, f32, "k")
+    if v is k:
+        vp, dvp = kp, None
+    else:
+        if v.shape != (B, S, Hkv, d_v) or dv is None or dv.shape != v.shape:
+            raise ValueError("v and dv must be [B, S, Hkv, d_v] (or v the very tensor passed as k)")
+        vp, dvp = _dev_ptr(v, f32, "v"), _dev_ptr(dv, f32, "dv")
+    rc = getattr(lib(), fn_name)(_dev_ptr(q, f32, "q"), kp, vp, _dev_ptr(out, f32, "out"), _dev_ptr(lse, f32, "lse"),
+                                 _dev_ptr(dout, f32, "dout"), _dev_ptr(dq, f32, "dq"), _dev_ptr(dk, f32, "dk"), dvp,
+                                 B, Hq, Hkv, S, d_qk, d_v, *pattern, float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_backward_f32(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_backward`."""
+    _backward_f32_common("loza_ssa_backward_f32", q, k, v, out, lse, dout, dq, dk, dv, (int(n_sink), _win(window)), scale, stream)
+
+
+def loza_ssa_backward_blocks_f32(q, k, v, out, lse, dout, dq, dk, dv, sink_blocks, local_blocks, block, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_backward_blocks`."""
+    _backward_f32_common("loza_ssa_backward_blocks_f32", q, k, v, out, lse, dout, dq, dk, dv,
+                         (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
 
 
 def loza_ssa_backward(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, scale, workspace, stream=None):

@@ -464,6 +464,50 @@ int loza_ssa_backward_blocks(const void *q, const void *k, const void *v, const 
                          true, scale, workspace, workspace_bytes, stream);
 }
 
+static int backward_f32(const float *q, const float *k, const float *v, const float *out, const float *lse, const float *dout,
+                        float *dq, float *dk, float *dv, int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                        int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream)
+{
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk) return LOZA_ERR_NULL;
+    if (int rc = check_common(B, Hq, Hkv, S, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
+    const bool alias = (v == k);
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (!alias && !dv) return LOZA_ERR_NULL;
+    if (d_qk > 256 || d_v > 256) return LOZA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) || !aligned16(dout) ||
+        !aligned16(dq) || !aligned16(dk) || (!alias && !aligned16(dv)))
+        return LOZA_ERR_ALIGN;
+    if (((int64_t)B * S * Hq + 3) / 4 > 2147483647LL) return LOZA_ERR_SHAPE;
+
+    loza::F32BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse; p.dout = dout;
+    p.dq = dq; p.dk = dk; p.dv = alias ? nullptr : dv;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.d_qk = d_qk; p.d_v = d_v;
+    p.k_row = d_qk; p.v_row = alias ? d_qk : d_v;
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S) : token_pattern(sink, local, S);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
+    p.scale = scale;
+    return loza::launch_backward_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *lse,
+                          const float *dout, float *dq, float *dk, float *dv,
+                          int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                          int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    return backward_f32(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, S, d_qk, d_v, n_sink, window, 1, false, scale, stream);
+}
+
+int loza_ssa_backward_blocks_f32(const float *q, const float *k, const float *v, const float *out, const float *lse,
+                                 const float *dout, float *dq, float *dk, float *dv,
+                                 int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
+                                 int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    return backward_f32(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, S, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                        scale, stream);
+}
+
 size_t loza_ssa_backward_workspace_bytes(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                                          int64_t n_sink, int64_t window, int v_aliases_k)
 {

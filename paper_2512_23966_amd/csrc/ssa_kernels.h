@@ -95,5 +95,19 @@ struct F32Params {
 };
 hipError_t launch_prefill_f32(const F32Params &p, hipStream_t stream);
 
+// fp32 backward: the forward's tensors plus the stored out and lse, the incoming gradient and the
+// three results (dv == nullptr: the values are a prefix of the key rows, dk holds the whole gradient)
+struct F32BwdParams {
+    const float *q, *k, *v, *out, *lse, *dout;
+    float *dq, *dk, *dv;
+    int B, Hq, Hkv;
+    int64_t S;
+    int d_qk, d_v;
+    int64_t k_row, v_row;
+    int n_sink, window, block;
+    float scale;
+};
+hipError_t launch_backward_f32(const F32BwdParams &p, hipStream_t stream);
+
 }  // namespace loza
 #endif

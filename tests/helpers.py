@@ -143,6 +143,62 @@ def oracle_forward_all(q, k, v, n_sink, window, scale, d_v, block=None):
     return out_t.to(torch.bfloat16).to(q.device), lse_t.to(torch.float32).to(q.device)
 
 
+def oracle_forward_all_f32(q, k, v, n_sink, window, scale, d_v, block=None):
+    """The same for fp32 tensors: out [B,S,Hq,d_v] and lse [B,Hq,S], both rounded to fp32."""
+    B, S, Hq, _ = q.shape
+    rb, rh, ri = all_rows(B, Hq, S)
+    out, lse = oracle_prefill_rows(q, k, v, rb, rh, ri, n_sink, window, scale, d_v, block)
+    out_t = torch.zeros(B, S, Hq, d_v, dtype=torch.float64)
+    out_t[torch.as_tensor(rb), torch.as_tensor(ri), torch.as_tensor(rh)] = torch.as_tensor(out)
+    lse_t = torch.zeros(B, Hq, S, dtype=torch.float64)
+    lse_t[torch.as_tensor(rb), torch.as_tensor(rh), torch.as_tensor(ri)] = torch.as_tensor(lse)
+    return out_t.to(torch.float32).to(q.device), lse_t.to(torch.float32).to(q.device)
+
+
+def run_backward_f32(q, k, v, out, lse, dout, n_sink, window, scale, block=None):
+    """HIP fp32 backward through the C ABI; outputs start as NaN (every element must be written)."""
+    alias = v is k
+    nan = float("nan")
+    dq = torch.full_like(q, nan)
+    dk = torch.full_like(k, nan)
+    dv = None if alias else torch.full_like(v, nan)
+    if block is None:
+        loza.loza_ssa_backward_f32(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, scale)
+    else:
+        loza.loza_ssa_backward_blocks_f32(q, k, v, out, lse, dout, dq, dk, dv, n_sink, window, block, scale)
+    torch.cuda.synchronize()
+    return dq, dk, dv
+
+
+# fp32 arithmetic throughout: dot products of up to 256 terms, expf of an argument of size ~10 (its
+# rounding alone is 1e-6 relative in the weight), sums over up to thousands of terms of mixed sign.
+# Bound per element: 4e-5 of the rms of its row (the size of the terms that were summed), 1e-5 of
+# the element, and a floor for rows that vanish by cancellation.
+def grad_tolerance_f32(ref: np.ndarray) -> np.ndarray:
+    row_rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    return 4e-5 * row_rms + 1e-5 * np.abs(ref) + 2e-6
+
+
+def compare_backward_f32(q, k, v, out, lse, dout, got, n_sink, window, scale, label="", block=None):
+    dq, dk, dv = got
+    d_v = dout.shape[3]
+    alias = v is k
+    w = oracle.INT64_MAX if window is None else window
+    varg = ("alias", d_v) if alias else v.cpu()
+    rq, rk, rv = oracle.ssa_backward(q.cpu(), k.cpu(), varg, dout.cpu(), n_sink=n_sink, window=w, scale=scale, block=block,
+                                     out=out.cpu(), lse=lse.cpu())
+    if alias:
+        rk = rk.copy()
+        rk[..., :d_v] += rv
+    for name, g, r in [("dq", dq, rq), ("dk", dk, rk)] + ([] if alias else [("dv", dv, rv)]):
+        gg = g.double().cpu().numpy()
+        assert np.isfinite(gg).all(), f"{label}: {name} has non-finite or unwritten elements"
+        err = np.abs(gg - r)
+        over = float((err - grad_tolerance_f32(r)).max())
+        print(f"[parity] {label}: {name} max|err|={err.max():.3e} max|ref|={np.abs(r).max():.3e}", flush=True)
+        assert over <= 0.0, f"{label}: {name} error exceeds its bound by {over} (max error {err.max()})"
+
+
 def run_backward(q, k, v, out, lse, dout, n_sink, window, scale, block=None):
     """HIP backward through the C ABI. Returns (dq, dk, dv); with ``v is k`` dk is the gradient of the
     shared tensor and dv is None. The outputs start as NaN: every element must be written."""

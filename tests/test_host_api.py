@@ -292,6 +292,20 @@ def test_backward_rejects_bad_arguments_and_sizes_its_workspace():
     assert B.loza_ssa_backward_workspace_bytes_blocks(1, 64, 1, 4096, 576, 512, 1, 7, 128, True) > 0
 
 
+def test_backward_f32_rejects_bad_arguments():
+    def call(q=FAKE, v=FAKE + 64, dv=FAKE, dout=FAKE, Hq=4, Hkv=2, S=100, d_qk=64, d_v=64, n_sink=3, window=10, scale=0.1):
+        return B.lib().loza_ssa_backward_f32(q, FAKE, v, FAKE, FAKE, dout, FAKE, FAKE, dv, 1, Hq, Hkv, S, d_qk, d_v,
+                                             n_sink, window, scale, None)
+    assert call(q=None) == ERR_NULL and call(dout=None) == ERR_NULL
+    assert call(dv=None) == ERR_NULL                     # separate values need their own dv
+    assert call(v=FAKE, dv=None, d_v=96) == ERR_SHAPE    # aliased values wider than the keys
+    assert call(window=0) == ERR_SHAPE and call(n_sink=-1) == ERR_SHAPE and call(Hq=3) == ERR_SHAPE
+    assert call(d_qk=257) == ERR_UNSUPPORTED and call(d_v=300) == ERR_UNSUPPORTED
+    assert call(dout=FAKE + 4) == ERR_ALIGN
+    assert B.lib().loza_ssa_backward_blocks_f32(FAKE, FAKE, FAKE + 64, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 2, 100, 64, 64,
+                                                1, 7, 0, 0.1, None) == ERR_SHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
