@@ -93,3 +93,27 @@ def test_backward_sweep(gpu_device, case):
     got = H.run_backward(q, k, v, out, lse, dout, ns, win, scale, block)
     H.compare_backward(q, k, v, out, lse, dout, got, ns, win, scale,
                        f"sweep {case}: Hq{Hq}/{Hkv} d{d_qk} alias{alias} S{S} ns{ns} W{win} b{block}", block)
+
+
+@pytest.mark.parametrize("case", range(400, 412))
+def test_f32_forward_and_backward_sweep(gpu_device, case):
+    """The fp32 twins: prefill, then the backward on out and lse taken from the oracle's forward."""
+    S, ns, win, block = _pattern(case)
+    S = min(S, 200)
+    r = np.random.default_rng(3000 + case)
+    Hq, Hkv = [(1, 1), (4, 2), (3, 1), (6, 6)][case % 4]
+    d_qk = int(r.choice([8, 24, 64, 100]))
+    alias = case % 3 == 0
+    d_v = int(r.integers(1, d_qk + 1)) if alias else int(r.choice([8, 40, 64]))
+    g = torch.Generator(device=gpu_device).manual_seed(7000 + case)
+    rnd = lambda *shape: torch.randn(shape, generator=g, device=gpu_device, dtype=torch.float32)
+    q, k, dout = rnd(1, S, Hq, d_qk), rnd(1, S, Hkv, d_qk), rnd(1, S, Hq, d_v)
+    v = k if alias else rnd(1, S, Hkv, d_v)
+    scale = d_qk ** -0.5
+    label = f"sweep {case}: f32 Hq{Hq}/{Hkv} d{d_qk}/{d_v} alias{alias} S{S} ns{ns} W{win} b{block}"
+    out, lse = H.run_prefill(q, k, v, ns, win, scale, d_v=d_v, block=block)
+    rb, rh, ri = H.all_rows(1, Hq, S)
+    H.compare_prefill(q, k, v, out, lse, rb, rh, ri, ns, win, scale, label, block=block)
+    o_ref, l_ref = H.oracle_forward_all_f32(q, k, v, ns, win, scale, d_v, block)
+    got = H.run_backward_f32(q, k, v, o_ref, l_ref, dout, ns, win, scale, block)
+    H.compare_backward_f32(q, k, v, o_ref, l_ref, dout, got, ns, win, scale, label, block)
