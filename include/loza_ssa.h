@@ -273,6 +273,20 @@ int loza_ssa_backward_blocks(const void *q, const void *k, const void *v, const 
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fp32 twins of loza_ssa_decode and loza_ssa_decode_blocks (same definition: the query of sequence b
+ * sits at position seqlens[b] - 1 of its cache; Architecture section, Eq. 2 / Eq. 4): fp32 in, fp32
+ * arithmetic, fp32 out, the layouts of the bf16 calls with float elements. Any d_qk, d_v in [1, 256];
+ * vcache may alias kcache with d_v <= d_qk; a length beyond S_max is cut to it; an empty cache gives
+ * out = 0 and lse = -inf. No workspace (one wavefront per query walks all of its live keys).
+ */
+int loza_ssa_decode_f32(const float *q, const float *kcache, const float *vcache, const int32_t *seqlens, float *out, float *lse,
+                        int B, int Hq, int Hkv, int64_t S_max, int d_qk, int d_v,
+                        int64_t n_sink, int64_t window, float scale, void *stream);
+int loza_ssa_decode_blocks_f32(const float *q, const float *kcache, const float *vcache, const int32_t *seqlens, float *out,
+                               float *lse, int B, int Hq, int Hkv, int64_t S_max, int d_qk, int d_v,
+                               int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
+
+/*
  * fp32 twins of loza_ssa_backward and loza_ssa_backward_blocks (the gradient of the paper's Eq. 4, as
  * above): fp32 in, fp32 arithmetic, fp32 out, the layouts of the bf16 calls with float elements; out
  * and lse are what loza_ssa_prefill_f32 returned. Any d_qk, d_v in [1, 256], any Hq / Hkv; v may alias

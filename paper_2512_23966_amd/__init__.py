@@ -16,4 +16,5 @@ from .binding import (  # noqa: F401
     loza_ssa_backward, loza_ssa_backward_blocks,
     loza_ssa_backward_workspace_bytes, loza_ssa_backward_workspace_bytes_blocks,
     loza_ssa_backward_f32, loza_ssa_backward_blocks_f32,
+    loza_ssa_decode_f32, loza_ssa_decode_blocks_f32,
 )

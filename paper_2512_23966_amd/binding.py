@@ -32,6 +32,7 @@ EXPORTS = (
     "loza_ssa_backward", "loza_ssa_backward_blocks",
     "loza_ssa_backward_workspace_bytes", "loza_ssa_backward_workspace_bytes_blocks",
     "loza_ssa_backward_f32", "loza_ssa_backward_blocks_f32",
+    "loza_ssa_decode_f32", "loza_ssa_decode_blocks_f32",
 )
 
 
@@ -95,6 +96,10 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_backward.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
         L.loza_ssa_backward_blocks.restype = ci
         L.loza_ssa_backward_blocks.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_decode_f32.restype = ci
+        L.loza_ssa_decode_f32.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
+        L.loza_ssa_decode_blocks_f32.restype = ci
+        L.loza_ssa_decode_blocks_f32.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp]
         L.loza_ssa_backward_f32.restype = ci
         L.loza_ssa_backward_f32.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_backward_blocks_f32.restype = ci
@@ -242,6 +247,35 @@ def loza_ssa_decode_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, lo
     ``loza_ssa_decode_workspace_bytes(..., sink_blocks * block, local_blocks * block)``."""
     _decode_common("loza_ssa_decode_blocks", q, kcache, vcache, seqlens, out, lse,
                    (int(sink_blocks), _win(local_blocks), int(block)), scale, workspace, stream)
+
+
+def _decode_f32_common(fn_name, q, kcache, vcache, seqlens, out, lse, pattern, scale, stream):
+    """fp32 SSA decode: the tensors of :func:`_decode_common` with float32 elements, no workspace."""
+    B, Hq, d_qk = q.shape
+    _, S_max, Hkv, _ = kcache.shape
+    d_v = out.shape[2]
+    if kcache.shape != (B, S_max, Hkv, d_qk) or out.shape != (B, Hq, d_v) or lse.shape != (B, Hq) or seqlens.shape != (B,):
+        raise ValueError("shape mismatch between q, kcache, seqlens, out, lse")
+    if vcache is not kcache and vcache.shape != (B, S_max, Hkv, d_v):
+        raise ValueError("vcache must be [B, S_max, Hkv, d_v] (or the very tensor passed as kcache)")
+    f32 = torch.float32
+    qp, kp = _dev_ptr(q, f32, "q"), _dev_ptr(kcache, f32, "kcache")
+    vp = kp if vcache is kcache else _dev_ptr(vcache, f32, "vcache")
+    rc = getattr(lib(), fn_name)(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, f32, "out"),
+                                 _dev_ptr(lse, f32, "lse"), B, Hq, Hkv, S_max, d_qk, d_v, *pattern, float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, fn_name)
+
+
+def loza_ssa_decode_f32(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_decode` (no workspace)."""
+    _decode_f32_common("loza_ssa_decode_f32", q, kcache, vcache, seqlens, out, lse, (int(n_sink), _win(window)), scale, stream)
+
+
+def loza_ssa_decode_blocks_f32(q, kcache, vcache, seqlens, out, lse, sink_blocks, local_blocks, block, scale, stream=None):
+    """fp32 twin of :func:`loza_ssa_decode_blocks` (no workspace)."""
+    _decode_f32_common("loza_ssa_decode_blocks_f32", q, kcache, vcache, seqlens, out, lse,
+                       (int(sink_blocks), _win(local_blocks), int(block)), scale, stream)
 
 
 def _decode_paged_common(fn_name, q, k_pages, v_pages, block_table, seqlens, out, lse, pattern, scale, workspace, stream):

@@ -306,6 +306,46 @@ static int prefill_f32(const float *q, const float *k, const float *v, float *ou
     return loza::launch_prefill_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 
+static int decode_f32(const float *q, const float *kcache, const float *vcache, const int32_t *seqlens, float *out, float *lse,
+                      int B, int Hq, int Hkv, int64_t S_max, int d_qk, int d_v,
+                      int64_t sink, int64_t local, int64_t block, bool blocks, float scale, void *stream)
+{
+    if (!q || !kcache || !vcache || !seqlens || !out || !lse) return LOZA_ERR_NULL;
+    if (int rc = check_common(B, Hq, Hkv, S_max, d_qk, d_v, sink, local, scale)) return rc;
+    if (blocks) { if (int rc = check_blocks(sink, local, block)) return rc; }
+    const bool alias = (vcache == kcache);
+    if (alias && d_v > d_qk) return LOZA_ERR_SHAPE;
+    if (d_qk > 256 || d_v > 256) return LOZA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(kcache) || !aligned16(vcache) || !aligned16(out) ||
+        (reinterpret_cast<uintptr_t>(seqlens) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return LOZA_ERR_ALIGN;
+    if (((int64_t)B * Hq + 3) / 4 > 2147483647LL) return LOZA_ERR_SHAPE;
+
+    loza::F32Params p{};
+    p.q = q; p.k = kcache; p.v = vcache; p.out = out; p.lse = lse; p.seqlens = seqlens;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S_max; p.d_qk = d_qk; p.d_v = d_v;
+    p.k_row = d_qk; p.v_row = alias ? d_qk : d_v;
+    const Pattern pat = blocks ? block_pattern(sink, local, block, S_max) : token_pattern(sink, local, S_max);
+    p.n_sink = pat.n_sink; p.window = pat.window; p.block = pat.block;
+    p.scale = scale;
+    return loza::launch_prefill_f32(p, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
+int loza_ssa_decode_f32(const float *q, const float *kcache, const float *vcache, const int32_t *seqlens, float *out, float *lse,
+                        int B, int Hq, int Hkv, int64_t S_max, int d_qk, int d_v,
+                        int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    return decode_f32(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false, scale, stream);
+}
+
+int loza_ssa_decode_blocks_f32(const float *q, const float *kcache, const float *vcache, const int32_t *seqlens, float *out,
+                               float *lse, int B, int Hq, int Hkv, int64_t S_max, int d_qk, int d_v,
+                               int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream)
+{
+    return decode_f32(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, sink_blocks, local_blocks, block, true,
+                      scale, stream);
+}
+
 size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v)
 {
     if (B < 1 || Hq < 1 || S < 1 || d_v < 1 || S > kMaxSeq) return 0;

@@ -20,13 +20,27 @@ __global__ __launch_bounds__(64 * F32_WAVES) void ssa_prefill_f32_kernel(const F
 {
     __shared__ float s_q[F32_WAVES][F32_MAX_D];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t n_rows = (int64_t)p.B * p.S * p.Hq;
+    const bool decode = p.seqlens != nullptr;
+    const int64_t n_rows = decode ? (int64_t)p.B * p.Hq : (int64_t)p.B * p.S * p.Hq;
     const int64_t r = (int64_t)blockIdx.x * F32_WAVES + wave;
     if (r >= n_rows) return;  // whole wavefront leaves together; no block-wide barrier is used
     const int h = (int)(r % p.Hq);
     const int64_t bi = r / p.Hq;
-    const int i = (int)(bi % p.S);
-    const int64_t b = bi / p.S;
+    int i;
+    int64_t b;
+    if (decode) {
+        b = bi;
+        const int64_t L = (int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S;  // a length beyond the cache is cut to it
+        if (L <= 0) {  // empty cache: out = 0, lse = -inf
+            for (int c = lane; c < p.d_v; c += 64) p.out[r * p.d_v + c] = 0.f;
+            if (lane == 0) p.lse[r] = -INFINITY;
+            return;
+        }
+        i = (int)(L - 1);
+    } else {
+        i = (int)(bi % p.S);
+        b = bi / p.S;
+    }
     const int g = h / (p.Hq / p.Hkv);
 
     const float *q = p.q + r * p.d_qk;
@@ -91,12 +105,12 @@ __global__ __launch_bounds__(64 * F32_WAVES) void ssa_prefill_f32_kernel(const F
         const int col = c * 64 + lane;
         if (col < p.d_v) o[col] = acc[c] * inv;
     }
-    if (lane == 0) p.lse[((int64_t)b * p.Hq + h) * p.S + i] = m + logf(l);
+    if (lane == 0) p.lse[decode ? r : ((int64_t)b * p.Hq + h) * p.S + i] = m + logf(l);
 }
 
 hipError_t launch_prefill_f32(const F32Params &p, hipStream_t stream)
 {
-    const int64_t n_rows = (int64_t)p.B * p.S * p.Hq;
+    const int64_t n_rows = p.seqlens ? (int64_t)p.B * p.Hq : (int64_t)p.B * p.S * p.Hq;
     const int64_t blocks = (n_rows + F32_WAVES - 1) / F32_WAVES;
     hipLaunchKernelGGL(ssa_prefill_f32_kernel, dim3((unsigned)blocks), dim3(64 * F32_WAVES), 0, stream, p);
     return hipGetLastError();

@@ -92,6 +92,9 @@ struct F32Params {
     int64_t k_row, v_row;  // elements per key / value row (v_row = d_qk when v aliases k)
     int n_sink, window, block;  // as in FwdParams
     float scale;
+    // decode form: one query per sequence at position seqlens[b] - 1 of its cache (k, v are then
+    // [B, S, Hkv, .] caches, q and out [B, Hq, .], lse [B, Hq]); nullptr: prefill
+    const int32_t *seqlens;
 };
 hipError_t launch_prefill_f32(const F32Params &p, hipStream_t stream);
 

@@ -65,6 +65,19 @@ def run_decode(q, kc, vc, seqlens, n_sink, window, scale, d_v=None, block=None):
     return out, lse
 
 
+def run_decode_f32(q, kc, vc, seqlens, n_sink, window, scale, d_v=None, block=None):
+    B, Hq, _ = q.shape
+    d_v = d_v if d_v is not None else vc.shape[3]
+    out = torch.full((B, Hq, d_v), float("nan"), dtype=torch.float32, device=q.device)
+    lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device=q.device)
+    if block is None:
+        loza.loza_ssa_decode_f32(q, kc, vc, seqlens, out, lse, n_sink, window, scale)
+    else:
+        loza.loza_ssa_decode_blocks_f32(q, kc, vc, seqlens, out, lse, n_sink, window, block, scale)
+    torch.cuda.synchronize()
+    return out, lse
+
+
 def oracle_prefill_rows(q, k, v, rb, rh, ri, n_sink, window, scale, d_v, block=None):
     """Oracle on the listed (b, h, i) rows, fed with the very bits the GPU tensors hold."""
     idx = (torch.as_tensor(rb, device=q.device), torch.as_tensor(ri, device=q.device), torch.as_tensor(rh, device=q.device))
@@ -125,7 +138,7 @@ def compare_decode(q, kc, vc, seqlens, out, lse, rb, rh, n_sink, window, scale, 
     got_out = out[torch.as_tensor(rb, device=dev), torch.as_tensor(rh, device=dev)].double().cpu().numpy()
     got_lse = lse[torch.as_tensor(rb, device=dev), torch.as_tensor(rh, device=dev)].double().cpu().numpy()
     assert np.isfinite(got_out).all(), f"{label}: non-finite output"
-    return _judge(got_out, ref_out, got_lse, ref_lse, torch.bfloat16, len(rb), label)
+    return _judge(got_out, ref_out, got_lse, ref_lse, out.dtype, len(rb), label)
 
 
 # ---- backward -------------------------------------------------------------------------------------

@@ -306,6 +306,18 @@ def test_backward_f32_rejects_bad_arguments():
                                                 1, 7, 0, 0.1, None) == ERR_SHAPE
 
 
+def test_decode_f32_rejects_bad_arguments():
+    def call(q=FAKE, vc=FAKE + 64, lens=FAKE, Hq=4, Hkv=2, S=100, d_qk=64, d_v=64, n_sink=3, window=10, scale=0.1):
+        return B.lib().loza_ssa_decode_f32(q, FAKE, vc, lens, FAKE, FAKE, 2, Hq, Hkv, S, d_qk, d_v, n_sink, window, scale, None)
+    assert call(q=None) == ERR_NULL and call(lens=None) == ERR_NULL
+    assert call(vc=FAKE, d_v=96) == ERR_SHAPE            # aliased values wider than the keys
+    assert call(window=0) == ERR_SHAPE and call(Hq=3) == ERR_SHAPE and call(S=0) == ERR_SHAPE
+    assert call(d_qk=257) == ERR_UNSUPPORTED
+    assert call(q=FAKE + 4) == ERR_ALIGN and call(lens=FAKE + 2) == ERR_ALIGN
+    assert B.lib().loza_ssa_decode_blocks_f32(FAKE, FAKE, FAKE + 64, FAKE, FAKE, FAKE, 2, 4, 2, 100, 64, 64,
+                                              1, 0, 16, 0.1, None) == ERR_SHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
