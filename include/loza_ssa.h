@@ -237,6 +237,20 @@ int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void
 size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v);
 
 /*
+ * Gradient of the calibration blend with respect to alpha (Architecture section, Eq. 3): the blend is
+ * alpha O + (1 - alpha) O', so d(alpha) = sum over every element of dout * (O - O').
+ *   dout, out_full, out_sparse: n bf16 elements each (device, 16-byte aligned): the gradient arriving
+ *       at the blend and the two outputs loza_ssa_prefill_calibration_blocks wrote; n >= 8, a multiple of 8
+ *   dalpha: one float on the device (overwritten)
+ *   workspace: loza_ssa_calibration_alpha_grad_workspace_bytes(n) bytes of device memory (0 for an n the
+ *       call rejects), 16-byte aligned, contents ignored
+ * Products and sums in fp64 in a fixed order (deterministic), one rounding to fp32 at the end.
+ */
+int loza_ssa_calibration_alpha_grad(const void *dout, const void *out_full, const void *out_sparse, float *dalpha, int64_t n,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+size_t loza_ssa_calibration_alpha_grad_workspace_bytes(int64_t n);
+
+/*
  * SSA backward: the gradients of loza_ssa_prefill's output with respect to q, k and v, over live
  * (query, key) pairs only. This is what training a sparsified model differentiates (paper:
  * Architecture section, Eq. 4 and its Training paragraph; the paper states no formulas, they are the

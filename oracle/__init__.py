@@ -177,6 +177,20 @@ def calibration_rows(q_rows, k, v, row_b, row_h, row_i, *, Hq, sink_blocks, loca
     return a * o_full + (1.0 - a) * o_sparse, o_full, o_sparse, lse_full, lse_sparse
 
 
+def calibration_alpha_grad(dout, o_full, o_sparse) -> float:
+    """Derivative of ``sum(dout * (alpha * O + (1 - alpha) * O'))`` with respect to alpha (the blend of
+    the Architecture section, Eq. 3): ``sum(dout * (O - O'))``, in float64."""
+    def widen(x):
+        if isinstance(x, np.ndarray) and x.dtype == np.float64:
+            return x
+        a = as_oracle_array(x)
+        if a.dtype == np.uint16:  # bf16 bit patterns: exact in float32
+            a = (a.astype(np.uint32) << 16).view(np.float32)
+        return a.astype(np.float64)
+    d, a, s = widen(dout), widen(o_full), widen(o_sparse)
+    return float(np.sum(d * (a - s)))
+
+
 def ssa_backward(q, k, v, dout, *, n_sink, window, scale, block=None, n_threads=None, out=None, lse=None):
     """Gradient of SSA (Eq. 4) with respect to Q, K and V for the scalar ``sum(dout * O)``.
 

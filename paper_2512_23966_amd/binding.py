@@ -33,6 +33,7 @@ EXPORTS = (
     "loza_ssa_backward_workspace_bytes", "loza_ssa_backward_workspace_bytes_blocks",
     "loza_ssa_backward_f32", "loza_ssa_backward_blocks_f32",
     "loza_ssa_decode_f32", "loza_ssa_decode_blocks_f32",
+    "loza_ssa_calibration_alpha_grad", "loza_ssa_calibration_alpha_grad_workspace_bytes",
 )
 
 
@@ -96,6 +97,10 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_backward.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
         L.loza_ssa_backward_blocks.restype = ci
         L.loza_ssa_backward_blocks.argtypes = [vp] * 9 + [ci, ci, ci, i64, ci, ci, i64, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_calibration_alpha_grad.restype = ci
+        L.loza_ssa_calibration_alpha_grad.argtypes = [vp, vp, vp, vp, i64, vp, sz, vp]
+        L.loza_ssa_calibration_alpha_grad_workspace_bytes.restype = sz
+        L.loza_ssa_calibration_alpha_grad_workspace_bytes.argtypes = [i64]
         L.loza_ssa_decode_f32.restype = ci
         L.loza_ssa_decode_f32.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_decode_blocks_f32.restype = ci
@@ -346,6 +351,24 @@ def loza_ssa_prefill_calibration_blocks(q, k, v, out, out_full, out_sparse, lse_
         _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     if rc != LOZA_OK:
         raise LozaError(rc, "loza_ssa_prefill_calibration_blocks")
+
+
+def loza_ssa_calibration_alpha_grad_workspace_bytes(n) -> int:
+    return int(lib().loza_ssa_calibration_alpha_grad_workspace_bytes(int(n)))
+
+
+def loza_ssa_calibration_alpha_grad(dout, out_full, out_sparse, dalpha, workspace, stream=None):
+    """d(alpha) of the calibration blend: sum of dout * (out_full - out_sparse). Three bf16 GPU tensors of
+    one shape, dalpha a float32 GPU tensor of one element, workspace uint8."""
+    if out_full.shape != dout.shape or out_sparse.shape != dout.shape or dalpha.numel() != 1:
+        raise ValueError("dout, out_full, out_sparse must share a shape; dalpha holds one element")
+    bf = torch.bfloat16
+    rc = lib().loza_ssa_calibration_alpha_grad(_dev_ptr(dout, bf, "dout"), _dev_ptr(out_full, bf, "out_full"),
+                                               _dev_ptr(out_sparse, bf, "out_sparse"), _dev_ptr(dalpha, torch.float32, "dalpha"),
+                                               dout.numel(), _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                               _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_calibration_alpha_grad")
 
 
 def _extend_common(fn_name, q, kcache, vcache, seqlens, out, lse, pattern, scale, stream):

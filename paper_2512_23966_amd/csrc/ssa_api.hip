@@ -383,6 +383,26 @@ int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void
                                    (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
 }
 
+size_t loza_ssa_calibration_alpha_grad_workspace_bytes(int64_t n)
+{
+    if (n < 8 || n % 8 != 0) return 0;
+    return (size_t)loza::alpha_grad_blocks(n) * sizeof(double);
+}
+
+int loza_ssa_calibration_alpha_grad(const void *dout, const void *out_full, const void *out_sparse, float *dalpha, int64_t n,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!dout || !out_full || !out_sparse || !dalpha) return LOZA_ERR_NULL;
+    const size_t need = loza_ssa_calibration_alpha_grad_workspace_bytes(n);
+    if (need == 0) return LOZA_ERR_SHAPE;
+    if (!workspace || workspace_bytes < need) return LOZA_ERR_WORKSPACE;
+    if (!aligned16(dout) || !aligned16(out_full) || !aligned16(out_sparse) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(dalpha) & 3u))
+        return LOZA_ERR_ALIGN;
+    return loza::launch_alpha_grad_bf16((const uint16_t *)dout, (const uint16_t *)out_full, (const uint16_t *)out_sparse, dalpha, n,
+                                        (double *)workspace, (hipStream_t)stream) == hipSuccess ? LOZA_OK : LOZA_ERR_HIP;
+}
+
 int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *out, float *lse,
                          int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                          int64_t n_sink, int64_t window, float scale, void *stream)

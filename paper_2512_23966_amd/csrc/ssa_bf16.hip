@@ -1006,6 +1006,68 @@ hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float a
     return hipGetLastError();
 }
 
+// Gradient of the calibration blend with respect to alpha (paper: Architecture section, Eq. 3):
+// d/d(alpha) [alpha O + (1 - alpha) O'] = O - O', so d(alpha) = sum over every element of
+// dout * (O - O'), from the bf16 tensors the blend wrote. Two launches and a fixed order of
+// addition (deterministic): per-workgroup partial sums in fp64, then one workgroup adds those.
+constexpr int kAlphaGradBlocks = 4096;
+
+static __device__ __forceinline__ double block_sum_256(double x, double *sm)
+{
+    sm[threadIdx.x] = x;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+        __syncthreads();
+    }
+    return sm[0];
+}
+
+__global__ __launch_bounds__(256) void ssa_alpha_grad_partial_kernel(const uint16_t *__restrict__ dout, const uint16_t *__restrict__ o_full,
+                                                                     const uint16_t *__restrict__ o_sparse, double *__restrict__ partial,
+                                                                     int64_t n8)
+{
+    __shared__ double sm[256];
+    auto widen = [](uint32_t bits) { return (double)__builtin_bit_cast(float, bits); };
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const u32x4 d = ((const u32x4 *)dout)[i], a = ((const u32x4 *)o_full)[i], s = ((const u32x4 *)o_sparse)[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc += widen(d[e] << 16) * (widen(a[e] << 16) - widen(s[e] << 16));
+            acc += widen(d[e] & 0xffff0000u) * (widen(a[e] & 0xffff0000u) - widen(s[e] & 0xffff0000u));
+        }
+    }
+    const double total = block_sum_256(acc, sm);
+    if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void ssa_alpha_grad_final_kernel(const double *__restrict__ partial, int n_partial, float *__restrict__ dalpha)
+{
+    __shared__ double sm[256];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < n_partial; i += 256) acc += partial[i];
+    const double total = block_sum_256(acc, sm);
+    if (threadIdx.x == 0) *dalpha = (float)total;
+}
+
+int alpha_grad_blocks(int64_t n)
+{
+    const int64_t n8 = n / 8, b = (n8 + 255) / 256;
+    return (int)(b < kAlphaGradBlocks ? (b < 1 ? 1 : b) : kAlphaGradBlocks);
+}
+
+hipError_t launch_alpha_grad_bf16(const uint16_t *dout, const uint16_t *o_full, const uint16_t *o_sparse, float *dalpha, int64_t n,
+                                  double *partial, hipStream_t stream)
+{
+    const int blocks = alpha_grad_blocks(n);
+    hipLaunchKernelGGL(ssa_alpha_grad_partial_kernel, dim3(blocks), dim3(256), 0, stream, dout, o_full, o_sparse, partial, n / 8);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(ssa_alpha_grad_final_kernel, dim3(1), dim3(256), 0, stream, (const double *)partial, blocks, dalpha);
+    return hipGetLastError();
+}
+
 bool bf16_shape_supported(int d_qk, int d_v, bool alias)
 {
     if (d_qk == 576 && d_v == 512) return alias;

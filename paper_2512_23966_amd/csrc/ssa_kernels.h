@@ -46,6 +46,11 @@ hipError_t launch_extend_bf16(const FwdParams &p, int d_qk, int d_v, bool alias,
 hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias, hipStream_t stream);
 hipError_t launch_blend_bf16(const float *o_full, const float *o_sparse, float alpha, uint16_t *out,
                              uint16_t *out_full, uint16_t *out_sparse, int64_t n, hipStream_t stream);
+// d(alpha) of the blend: sum of dout * (O - O') over n bf16 elements (n a multiple of 8); `partial`
+// holds alpha_grad_blocks(n) doubles of scratch
+int alpha_grad_blocks(int64_t n);
+hipError_t launch_alpha_grad_bf16(const uint16_t *dout, const uint16_t *o_full, const uint16_t *o_sparse, float *dalpha, int64_t n,
+                                  double *partial, hipStream_t stream);
 
 // Arguments of the bf16 backward kernels. Pattern fields as in FwdParams.
 struct BwdParams {

@@ -102,3 +102,49 @@ def test_calibration_paper_sizes_mla_32k(gpu_device):
     like = replace(cfg, n_sink=128, window=896)
     rb, rh, ri = W.sample_rows(like, n_random=96, n_heads=3)
     _compare(q, k, v, res, rb, rh, ri, 1, 7, 128, 0.5, cfg.scale, "calib mla 32K s1 l7 b128")
+
+
+@pytest.mark.parametrize("shape,seed", [((8,), 1), ((3, 7, 2, 8), 2), ((1, 700, 8, 128), 3), ((2, 4096, 64, 8 * 9), 4)])
+def test_alpha_gradient(gpu_device, shape, seed):
+    """d(alpha) = sum(dout * (O - O')) on synthetic bf16 tensors (one element up to 4.7 million elements per
+    workgroup partial), against the oracle's float64 sum; the only rounding is the final one to fp32."""
+    dout, o_full, o_sparse = (_rand(shape, 100 * seed + i, torch.bfloat16, gpu_device) for i in range(3))
+    dalpha = torch.full((1,), float("nan"), dtype=torch.float32, device=gpu_device)
+    n = dout.numel()
+    ws = torch.empty(loza.loza_ssa_calibration_alpha_grad_workspace_bytes(n), dtype=torch.uint8, device=gpu_device)
+    loza.loza_ssa_calibration_alpha_grad(dout, o_full, o_sparse, dalpha, ws)
+    torch.cuda.synchronize()
+    ref = oracle.calibration_alpha_grad(dout, o_full, o_sparse)
+    got = float(dalpha.item())
+    scale = float(np.sqrt(n)) * 2.0   # size of a sum of n products of N(0,1) values times N(0,2)
+    print(f"[parity] alpha gradient n={n}: got {got:.9g} ref {ref:.9g}", flush=True)
+    assert abs(got - ref) <= 2.0 ** -23 * max(abs(ref), 1e-30) + 1e-12 * scale
+    again = torch.empty_like(dalpha)
+    loza.loza_ssa_calibration_alpha_grad(dout, o_full, o_sparse, again, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(again, dalpha)                      # deterministic
+
+
+def test_alpha_gradient_after_the_calibration_forward(gpu_device):
+    """The tensors the calibration forward wrote, fed to the gradient; held against the oracle's two
+    attentions (unrounded), so the bound is the bf16 rounding of O and O' summed over the elements."""
+    B, S, Hq, s, l, b, alpha = 1, 300, 64, 1, 2, 32, 0.3
+    q = _rand((B, S, Hq, 576), 51, torch.bfloat16, gpu_device)
+    k = _rand((B, S, 1, 576), 52, torch.bfloat16, gpu_device)
+    scale = 192 ** -0.5
+    out, o_full, o_sparse, _, _ = _run(q, k, k, s, l, b, alpha, scale, 512)
+    dout = _rand(out.shape, 53, torch.bfloat16, gpu_device)
+    dalpha = torch.empty(1, dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(loza.loza_ssa_calibration_alpha_grad_workspace_bytes(out.numel()), dtype=torch.uint8, device=gpu_device)
+    loza.loza_ssa_calibration_alpha_grad(dout, o_full, o_sparse, dalpha, ws)
+    torch.cuda.synchronize()
+    rb, rh, ri = H.all_rows(B, Hq, S)
+    qr = q[torch.as_tensor(rb, device=gpu_device), torch.as_tensor(ri, device=gpu_device), torch.as_tensor(rh, device=gpu_device)].contiguous().cpu()
+    _, r_full, r_sparse, _, _ = oracle.calibration_rows(qr, k.cpu(), ("alias", 512), rb, rh, ri, Hq=Hq, sink_blocks=s, local_blocks=l,
+                                                        block=b, alpha=alpha, scale=scale)
+    d_rows = dout[torch.as_tensor(rb, device=gpu_device), torch.as_tensor(ri, device=gpu_device), torch.as_tensor(rh, device=gpu_device)].double().cpu().numpy()
+    ref = oracle.calibration_alpha_grad(d_rows, r_full, r_sparse)
+    # each of the n terms carries the rounding of O and of O' (and the kernels' own 1e-2-bounded error): a random sum
+    bound = 6.0 * np.sqrt(d_rows.size) * 2.0 ** -8 * float(np.abs(d_rows).mean()) * float(np.abs(r_full).mean() + np.abs(r_sparse).mean())
+    print(f"[parity] alpha gradient after the forward: got {float(dalpha.item()):.6g} ref {ref:.6g} bound {bound:.3g}", flush=True)
+    assert abs(float(dalpha.item()) - ref) <= bound

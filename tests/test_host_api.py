@@ -318,6 +318,18 @@ def test_decode_f32_rejects_bad_arguments():
                                               1, 0, 16, 0.1, None) == ERR_SHAPE
 
 
+def test_alpha_gradient_rejects_bad_arguments_and_sizes_its_workspace():
+    call = lambda d=FAKE, dalpha=FAKE, n=4096, ws=FAKE, wsb=1 << 20: B.lib().loza_ssa_calibration_alpha_grad(
+        d, FAKE, FAKE, dalpha, n, ws, wsb, None)
+    assert call(d=None) == ERR_NULL and call(dalpha=None) == ERR_NULL
+    assert call(n=0) == ERR_SHAPE and call(n=12) == ERR_SHAPE
+    assert call(ws=None) == ERR_WORKSPACE and call(wsb=8) == ERR_WORKSPACE
+    assert call(d=FAKE + 8) == ERR_ALIGN and call(dalpha=FAKE + 2) == ERR_ALIGN
+    assert B.loza_ssa_calibration_alpha_grad_workspace_bytes(12) == 0
+    assert B.loza_ssa_calibration_alpha_grad_workspace_bytes(8) == 8                  # one workgroup, one double
+    assert B.loza_ssa_calibration_alpha_grad_workspace_bytes(1 << 33) == 4096 * 8     # never more than 4096 partial sums
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")

@@ -173,3 +173,19 @@ def test_calibration_against_library_attention_under_set_built_masks():
     sparse = torch.nn.functional.scaled_dot_product_attention(qd, kd, vd, attn_mask=sparse_mask, scale=scale)
     ref = (alpha * full + (1 - alpha) * sparse)[0].numpy()          # [Hq, S, dv]
     np.testing.assert_allclose(blend.reshape(Hq, S, -1), ref, atol=1e-12)
+
+
+def test_alpha_gradient_is_the_slope_of_the_blend():
+    """d/d(alpha) of sum(dout * blend(alpha)) by the difference of two blends (the blend is linear in
+    alpha, so the difference quotient is exact up to rounding), and two closed forms."""
+    _, (b0, full, sparse, _, _) = _calib_case(0.2)
+    _, (b1, _, _, _, _) = _calib_case(0.7)
+    dout = np.random.default_rng(5).standard_normal(full.shape)
+    slope = (np.sum(dout * b1) - np.sum(dout * b0)) / 0.5
+    got = oracle.calibration_alpha_grad(dout, full, sparse)
+    assert abs(got - slope) <= 1e-12 * max(1.0, abs(slope))
+    assert oracle.calibration_alpha_grad(dout, full, full) == 0.0
+    assert oracle.calibration_alpha_grad(np.ones_like(full), full, np.zeros_like(full)) == pytest.approx(full.sum(), rel=1e-14)
+    # bf16 and float32 tensors are widened exactly
+    t = torch.tensor([[1.5, -2.0], [0.25, 3.0]])
+    assert oracle.calibration_alpha_grad(t.to(torch.bfloat16), t, torch.zeros(2, 2)) == 1.5 ** 2 + 4.0 + 0.0625 + 9.0
