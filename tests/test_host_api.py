@@ -330,6 +330,36 @@ def test_alpha_gradient_rejects_bad_arguments_and_sizes_its_workspace():
     assert B.loza_ssa_calibration_alpha_grad_workspace_bytes(1 << 33) == 4096 * 8     # never more than 4096 partial sums
 
 
+def test_the_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """gcc -std=c99 -pedantic -Werror on a program that includes the header, links the library and calls
+    the host-only entry points; its output must agree with the Python binding's."""
+    import shutil
+    import subprocess
+    from pathlib import Path
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = Path(__file__).resolve().parents[1]
+    lib_dir = Path(B.LIB_PATH).parent
+    exe = tmp_path / "abi_host"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", str(root / "include"),
+                    str(root / "tests" / "c" / "abi_host.c"), "-o", str(exe), "-L", str(lib_dir), "-lloza_ssa",
+                    f"-Wl,-rpath,{lib_dir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines()
+    got = {line.split()[0]: line.split()[1:] for line in out}
+    assert got["live_ranges"] == ["0"] + [str(x) for x in B.loza_ssa_live_ranges(10000, 128, 512)]
+    assert got["live_ranges_blocks"] == ["0"] + [str(x) for x in B.loza_ssa_live_ranges_blocks(1000, 1, 7, 128)]
+    assert got["live_pairs"] == [str(B.loza_ssa_live_pairs(131072, 128, 8192))]
+    assert got["live_pairs_blocks"] == [str(B.loza_ssa_live_pairs_blocks(131072, 1, 7, 128))]
+    assert got["decode_splits"] == [str(B.loza_ssa_decode_num_splits(64, 64, 1, 262144, 128, 8192))]
+    assert got["decode_ws"] == [str(B.loza_ssa_decode_workspace_bytes(64, 64, 1, 262144, 512, 128, 8192))]
+    assert got["backward_ws"] == [str(B.loza_ssa_backward_workspace_bytes(1, 64, 1, 131072, 576, 512, 128, 8192, True))]
+    assert got["calibration_ws"] == [str(B.loza_ssa_calibration_workspace_bytes(1, 64, 4096, 512))]
+    assert got["alpha_grad_ws"] == [str(B.loza_ssa_calibration_alpha_grad_workspace_bytes(4096))]
+    assert got["null_q"] == [str(ERR_NULL)]
+    assert " ".join(got["status"]) == B.loza_status_str(ERR_WORKSPACE)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", tmp_path / "nope.so")
