@@ -12,6 +12,7 @@ namespace {
 
 constexpr int kComputeUnits = 256;              // MI355X
 constexpr int64_t kMaxSeq = 2147483647LL - 128;  // positions are 32-bit inside the kernels
+constexpr int kMaxSplits = 64;                   // key splits of a decode query, at most
 
 inline bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
 
@@ -33,16 +34,18 @@ int decode_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t
     const int G = Hq / Hkv;
     const int rows = loza::decode_rows_per_tile();
     const int64_t base = (int64_t)B * Hkv * ((G + rows - 1) / rows);
-    int64_t live = n_sink + (window < S_max ? window : S_max);
+    // both terms are cut to S_max before they are added: either may be INT64_MAX
+    int64_t live = (n_sink < S_max ? n_sink : S_max) + (window < S_max ? window : S_max);
     if (live > S_max) live = S_max;
     const int64_t tiles = (live + 63) / 64 + 2;
     int64_t n = (kComputeUnits + base - 1) / base;  // one workgroup per compute unit at least
+    // LOZA_DECODE_SPLITS (documented in the header): another split count, for tests and experiments
     if (const char *env = getenv("LOZA_DECODE_SPLITS")) {
         const long v = strtol(env, nullptr, 10);
-        if (v >= 1) n = v;
+        if (v >= 1 && v <= kMaxSplits) n = v;
     }
     if (n > tiles) n = tiles;
-    if (n > 64) n = 64;
+    if (n > kMaxSplits) n = kMaxSplits;
     if (n < 1) n = 1;
     return (int)n;
 }
@@ -73,12 +76,12 @@ int check_blocks(int64_t sink_blocks, int64_t local_blocks, int64_t block)
     return (sink_blocks < 0 || local_blocks < 1 || block < 1) ? LOZA_ERR_SHAPE : LOZA_OK;
 }
 
+// The reference maximum of the online softmax is the exact running maximum over the first 8 key
+// tiles of a row tile and afterwards moves only when exceeded by more than 2^8 (fp32 has the headroom).
 void set_rescale_policy(loza::FwdParams &p)
 {
     p.exact_tiles = 8;
     p.lazy_log2 = 8.0f;
-    if (const char *e = getenv("LOZA_EXACT_TILES")) p.exact_tiles = atoi(e);
-    if (const char *e = getenv("LOZA_LAZY_LOG2")) p.lazy_log2 = (float)atof(e);
 }
 
 }  // namespace

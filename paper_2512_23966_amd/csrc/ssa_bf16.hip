@@ -52,7 +52,7 @@ namespace loza {
 //   accumulators (d_v / 2 columns of all rows each) and run the value phase. Neither role needs
 //   the other's registers, so both fit, and the two phases of consecutive tiles overlap on
 //   different SIMDs.
-template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false>
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE>
 struct TileCfg {
     static constexpr int M = 32 * RB;            // query rows per workgroup
     static constexpr int N = 32;                 // keys per tile
@@ -89,8 +89,9 @@ struct TileCfg {
     static constexpr int NSTAGE = DECODE ? 4 : 3;
     // copy instructions one wave issues per tile, at least (waves differ by at most one)
     static constexpr int MIN_COPIES = (K_INSTR - 2 * SC) / NCW + V_INSTR / NCW;
-    // PRECISE: P is handed over as two bf16 terms (p = hi + lo), each with its own buffer pair
-    static constexpr int NPBUF = 2 * (PRECISE ? 2 : 1);
+    // A prefill tile can be (re)computed with P handed over as two bf16 terms (p = hi + lo), each with
+    // its own buffer pair; the decode's split kernel never does that (and has no room for it)
+    static constexpr int NPBUF = DECODE ? 2 : 4;
     static constexpr int PLO = 2;                // index offset of the low-term buffers
     static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
     static constexpr int PBYTES = M * PROW;
@@ -98,16 +99,18 @@ struct TileCfg {
     static constexpr int OFF_ALPHA = OFF_P + NPBUF * PBYTES;      // float[2][M]
     static constexpr int OFF_FLAG = OFF_ALPHA + 2 * M * 4;        // int[2][4] (one per row block, padded)
     static constexpr int OFF_LPART = OFF_FLAG + 2 * 16;           // float[2][M]
-    static constexpr int LDS_BYTES = OFF_LPART + 2 * M * 4;
+    static constexpr int OFF_REDO = OFF_LPART + 2 * M * 4;        // int: the tile has to be computed again, with two-term P
+    static constexpr int LDS_BYTES = OFF_REDO + 16;
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
-template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE = false, bool OUTF32 = false, bool EXT = false>
-__global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
+// One pass over one workgroup tile. PRECISE: P goes to the value phase as two bf16 terms. Returns
+// true (the same in every wave) when the tile has been left unwritten for a PRECISE pass.
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool PRECISE, bool OUTF32, bool EXT>
+static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *smem)
 {
-    using C = TileCfg<DQK, DV, RB, ALIAS, DECODE, PRECISE>;
+    using C = TileCfg<DQK, DV, RB, ALIAS, DECODE>;
     constexpr int M = C::M, N = C::N, NSTAGE = C::NSTAGE;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, lh = lane >> 5;
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
         const int64_t se = n_sink < L ? n_sink : L;
         const int64_t wb = L > 0 ? window_begin_of((int)(L - 1), p.window, p.block) : 0;
         const int64_t n_live = se + (L - (wb > se ? wb : se));
-        if (n_live < kDirectKeys) return;
+        if (n_live < kDirectKeys) return false;
     }
 
     // ---- the query row this lane scores ---------------------------------------------------------
@@ -169,8 +172,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     const int i_row = DECODE ? (int)(L - 1) : (int)(pos0 + r_row);
     const int i_min = DECODE ? (int)(L - 1) : (int)(pos0 + r0 / G);
     const int i_max = DECODE ? (int)(L - 1) : (int)(pos0 + ((r0 + M - 1 < R) ? r0 + M - 1 : R - 1) / G);
-    // an extend launch runs both variants of the kernel over all tiles; each tile belongs to one
-    if (!DECODE && extend && !p.all_precise && ((i_min < kPrecisePositions) != PRECISE)) return;
+    // Tiles among the first positions, and every tile of a pattern that leaves all rows few live keys,
+    // take the two-term pass right away.
+    if (!DECODE && !PRECISE && (p.all_precise || i_min < kPrecisePositions)) return true;
 
     bf16x8 qf[DQK / 16];
 
@@ -333,7 +337,9 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     int *s_flag = (int *)(smem + C::OFF_FLAG);
     float *s_lpart = (float *)(smem + C::OFF_LPART);
     char *s_p = smem + C::OFF_P;
+    int *s_redo = (int *)(smem + C::OFF_REDO);
     if (tid < 8) s_flag[tid] = 0;  // the padding entries of the flag words never ask for a rescale
+    if (!PRECISE && tid == 8) *s_redo = 0;
 
     // ---- scores of one tile: S^T[32 keys][32 rows of block wr] ------------------------------------
     // One inline-asm statement (score_asm.h): key fragment kk + DEPTH is fetched from LDS while
@@ -709,6 +715,27 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
     }
     lds_barrier();
 
+    if (!DECODE && !PRECISE) {
+        // A result of magnitude 2 or more leaves the error budget little beyond its own rounding to
+        // bf16 (half an ulp is 2^-7 there), and it can only come from a row whose weight sits on a few
+        // keys, where the rounding of P to bf16 shows most. A tile with such a row is not written: it
+        // is computed again with two-term P (the caller runs the PRECISE pass when this one says so).
+        bool big = false;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const float rsum = s_lpart[M + rb * 32 + ln];
+            float mx = 0.f;
+#pragma unroll
+            for (int db = 0; db < C::DVB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, __builtin_fabsf(o[db][rb][e]));
+            big = big || (rsum > 0.f && mx >= kRedoMagnitude * rsum && r0 + rb * 32 + ln < R);
+        }
+        if (__any(big) && lane == 0) *s_redo = 1;
+        lds_barrier();
+        if (*(volatile int *)s_redo) return true;
+    }
+
     if (!DECODE) {
         // lse = ln(sum_j exp(scale q.k_j)) = (m_ref + log2 l) * ln 2
         if (scorer && lh == 0 && my_row < R) {
@@ -781,6 +808,109 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
             }
         }
     }
+    return false;
+}
+
+// Prefill / extend: every tile is computed with P rounded to bf16 once; a tile that cannot afford
+// that (few live keys per row, or a result large enough that its own rounding fills the error
+// budget) is computed with two-term P instead. Decode: one pass of the split kernel.
+template <int DQK, int DV, int RB, bool ALIAS, bool DECODE, bool OUTF32 = false, bool EXT = false>
+__global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    if constexpr (DECODE) {
+        ssa_fwd_tile<DQK, DV, RB, ALIAS, true, false, false, false>(p, smem);
+    } else {
+        if (ssa_fwd_tile<DQK, DV, RB, ALIAS, false, false, OUTF32, EXT>(p, smem))
+            ssa_fwd_tile<DQK, DV, RB, ALIAS, false, true, OUTF32, EXT>(p, smem);
+    }
+}
+
+// One decode query computed from the cache rows themselves: scores, softmax and weighted sum in fp32
+// (no rounding of the weights). All threads of the workgroup (one per four output columns) call it
+// together. The live keys are walked twice, in chunks of kDirectKeys: once for the maximum of the
+// scores, once for the weights and the weighted sum (a query whose keys fit one chunk keeps its
+// scores between the two). n_live >= 1.
+template <int DQK, int DV>
+static __device__ void decode_row_direct(const FwdParams &p, int64_t h, int b, int g, int64_t se, int64_t wb, int64_t n_live)
+{
+    constexpr int NT = DV / 4;
+    __shared__ float s_w[kDirectKeys];
+    __shared__ __attribute__((aligned(16))) float s_q[DQK];
+    __shared__ float s_m[NT];
+    const int tid = threadIdx.x, c = tid * 4;
+    const int64_t k_step = (int64_t)p.Hkv * DQK;
+    const bool alias = (p.v == p.k);
+    const int64_t v_step = (int64_t)p.Hkv * (alias ? DQK : DV);
+    const bool paged = p.block_table != nullptr;
+    const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
+    const uint16_t *kb = p.k + (seq_row0 * p.Hkv + g) * DQK;
+    const uint16_t *vb = p.v + (seq_row0 * p.Hkv + g) * (alias ? DQK : DV);
+    // cache row of the t-th live key (through the block table of a paged cache)
+    auto key_of = [&](int64_t t) {
+        const int64_t j = t < se ? t : wb + (t - se);
+        if (!paged) return j;
+        int pid = p.block_table[(int64_t)b * p.max_pages + (j >> p.page_shift)];
+        pid = pid < 0 ? 0 : (pid < p.num_pages ? pid : p.num_pages - 1);
+        return ((int64_t)pid << p.page_shift) + (j & ((1 << p.page_shift) - 1));
+    };
+    auto lo16 = [](uint32_t w) { return __builtin_bit_cast(float, w << 16); };
+    auto hi16 = [](uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); };
+    const uint16_t *q = p.q + h * DQK;
+    for (int e = tid; e < DQK; e += NT) s_q[e] = __builtin_bit_cast(float, (uint32_t)q[e] << 16);
+    __syncthreads();
+    // scale * log2(e) * q . k of the t-th live key
+    auto score = [&](int64_t t) {
+        const u32x4 *kr = (const u32x4 *)(kb + key_of(t) * k_step);
+        float dot = 0.f;
+#pragma unroll 2
+        for (int c8 = 0; c8 < DQK / 8; ++c8) {
+            const u32x4 w = kr[c8];
+            const float4 qa = *(const float4 *)(s_q + 8 * c8), qb = *(const float4 *)(s_q + 8 * c8 + 4);
+            dot = __builtin_fmaf(qa.x, lo16(w[0]), dot);
+            dot = __builtin_fmaf(qa.y, hi16(w[0]), dot);
+            dot = __builtin_fmaf(qa.z, lo16(w[1]), dot);
+            dot = __builtin_fmaf(qa.w, hi16(w[1]), dot);
+            dot = __builtin_fmaf(qb.x, lo16(w[2]), dot);
+            dot = __builtin_fmaf(qb.y, hi16(w[2]), dot);
+            dot = __builtin_fmaf(qb.z, lo16(w[3]), dot);
+            dot = __builtin_fmaf(qb.w, hi16(w[3]), dot);
+        }
+        return dot * p.scale_log2;
+    };
+    const bool one_chunk = n_live <= kDirectKeys;
+    float m = LOZA_NEG_INF;
+    for (int64_t t = tid; t < n_live; t += NT) {
+        const float sc = score(t);
+        if (one_chunk) s_w[t] = sc;
+        m = fmaxf(m, sc);
+    }
+    s_m[tid] = m;
+    __syncthreads();
+    for (int t = 0; t < NT; ++t) m = fmaxf(m, s_m[t]);
+    float l = 0.f;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t c0 = 0; c0 < n_live; c0 += kDirectKeys) {
+        const int cnt = (int)(n_live - c0 < kDirectKeys ? n_live - c0 : kDirectKeys);
+        for (int t = tid; t < cnt; t += NT) s_w[t] = __builtin_amdgcn_exp2f((one_chunk ? s_w[t] : score(c0 + t)) - m);
+        __syncthreads();
+        for (int t = 0; t < cnt; ++t) {
+            const float w = s_w[t];
+            const u32x2 vr = *(const u32x2 *)(vb + key_of(c0 + t) * v_step + c);
+            l += w;
+            acc.x = __builtin_fmaf(w, lo16(vr[0]), acc.x);
+            acc.y = __builtin_fmaf(w, hi16(vr[0]), acc.y);
+            acc.z = __builtin_fmaf(w, lo16(vr[1]), acc.z);
+            acc.w = __builtin_fmaf(w, hi16(vr[1]), acc.w);
+        }
+        __syncthreads();
+    }
+    const float inv = 1.0f / l;
+    u32x2 w2;
+    w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
+    w2[1] = pack_bf16(acc.z * inv, acc.w * inv);
+    *(u32x2 *)(p.out + h * DV + c) = w2;
+    if (tid == 0) p.lse[h] = (m + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f;
 }
 
 // Merge of the key splits of one decode query (log-sum-exp rule, fixed split order). Each split s
@@ -788,80 +918,33 @@ __global__ __launch_bounds__(256) void ssa_fwd_kernel(const FwdParams p)
 // sum r_s of the same values as rounded to bf16 (what O_s was accumulated from):
 //   m* = max_s m_s ;  w_s = 2^(m_s - m*) ;  out = sum_s w_s O_s / sum_s w_s r_s ;
 //   lse = (m* + log2 sum_s w_s l_s) ln 2.
-// One workgroup per (sequence, query head), one thread per four output columns. A query with fewer
-// than kDirectKeys live keys never went through the split kernel: it is computed here from the
-// cache rows themselves, scores, softmax and weighted sum in fp32.
+// One workgroup per (sequence, query head), one thread per four output columns. Two kinds of query
+// are computed here from the cache rows instead (decode_row_direct): one with fewer than kDirectKeys
+// live keys, which never went through the split kernel, and one whose merged result reaches
+// kRedoMagnitude in some column (the weights of the split kernel are rounded to bf16, which a result
+// that large cannot afford).
 template <int DQK, int DV>
 __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParams p)
 {
-    constexpr int NT = DV / 4;
     const int64_t h = blockIdx.x;  // flat (b, query head)
     const int c = threadIdx.x * 4;
     const int n_splits = p.n_splits;
     uint16_t *out = p.out + h * DV + c;
 
-    // ---- few live keys: the whole query here, in fp32 (the split kernel skipped it) --------------
     const int b = (int)(h / p.Hq), hq = (int)(h - (int64_t)b * p.Hq), g = hq / p.G;
     const int64_t L = (int64_t)p.seqlens[b] < p.S ? (int64_t)p.seqlens[b] : p.S;
     const int64_t se = p.n_sink < L ? p.n_sink : L;
     int64_t wb = L > 0 ? window_begin_of((int)(L - 1), p.window, p.block) : 0;
     if (wb < se) wb = se;
     const int64_t n_live = se + (L - wb);
+    if (n_live <= 0) {  // empty cache
+        u32x2 z; z[0] = 0; z[1] = 0;
+        *(u32x2 *)out = z;
+        if (threadIdx.x == 0) p.lse[h] = LOZA_NEG_INF;
+        return;
+    }
     if (n_live < kDirectKeys) {
-        if (n_live <= 0) {  // empty cache
-            u32x2 z; z[0] = 0; z[1] = 0;
-            *(u32x2 *)out = z;
-            if (threadIdx.x == 0) p.lse[h] = LOZA_NEG_INF;
-            return;
-        }
-        __shared__ float s_w[kDirectKeys];
-        const int n = (int)n_live;
-        const uint16_t *q = p.q + h * DQK;
-        const int64_t k_step = (int64_t)p.Hkv * DQK;
-        const bool alias = (p.v == p.k);
-        const int64_t v_step = (int64_t)p.Hkv * (alias ? DQK : DV);
-        const bool paged = p.block_table != nullptr;
-        const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
-        const uint16_t *kb = p.k + (seq_row0 * p.Hkv + g) * DQK;
-        const uint16_t *vb = p.v + (seq_row0 * p.Hkv + g) * (alias ? DQK : DV);
-        // cache row of the t-th live key (through the block table of a paged cache)
-        auto key_of = [&](int t) {
-            const int64_t j = t < se ? (int64_t)t : wb + (t - se);
-            if (!paged) return j;
-            int pid = p.block_table[(int64_t)b * p.max_pages + (j >> p.page_shift)];
-            pid = pid < 0 ? 0 : (pid < p.num_pages ? pid : p.num_pages - 1);
-            return ((int64_t)pid << p.page_shift) + (j & ((1 << p.page_shift) - 1));
-        };
-        auto widen = [](uint16_t x) { return __builtin_bit_cast(float, (uint32_t)x << 16); };
-        for (int t = threadIdx.x; t < n; t += NT) {
-            const uint16_t *kr = kb + key_of(t) * k_step;
-            float dot = 0.f;
-            for (int e = 0; e < DQK; ++e) dot = __builtin_fmaf(widen(q[e]), widen(kr[e]), dot);
-            s_w[t] = dot * p.scale_log2;
-        }
-        __syncthreads();
-        float m = LOZA_NEG_INF;
-        for (int t = 0; t < n; ++t) m = fmaxf(m, s_w[t]);
-        __syncthreads();
-        for (int t = threadIdx.x; t < n; t += NT) s_w[t] = __builtin_amdgcn_exp2f(s_w[t] - m);
-        __syncthreads();
-        float l = 0.f;
-        float4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int t = 0; t < n; ++t) {
-            const float w = s_w[t];
-            const uint16_t *vr = vb + key_of(t) * v_step + c;
-            l += w;
-            acc.x = __builtin_fmaf(w, widen(vr[0]), acc.x);
-            acc.y = __builtin_fmaf(w, widen(vr[1]), acc.y);
-            acc.z = __builtin_fmaf(w, widen(vr[2]), acc.z);
-            acc.w = __builtin_fmaf(w, widen(vr[3]), acc.w);
-        }
-        const float inv = 1.0f / l;
-        u32x2 w2;
-        w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
-        w2[1] = pack_bf16(acc.z * inv, acc.w * inv);
-        *(u32x2 *)out = w2;
-        if (threadIdx.x == 0) p.lse[h] = (m + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f;
+        decode_row_direct<DQK, DV>(p, h, b, g, se, wb, n_live);
         return;
     }
 
@@ -879,29 +962,20 @@ __global__ __launch_bounds__(DV / 4) void ssa_decode_merge_kernel(const FwdParam
         acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
     }
     const float inv = 1.0f / den_r;
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    const bool big = fmaxf(fmaxf(__builtin_fabsf(acc.x), __builtin_fabsf(acc.y)), fmaxf(__builtin_fabsf(acc.z), __builtin_fabsf(acc.w))) >= kRedoMagnitude;
+    if (__syncthreads_or(big)) {
+        decode_row_direct<DQK, DV>(p, h, b, g, se, wb, n_live);
+        return;
+    }
     u32x2 w2;
-    w2[0] = pack_bf16(acc.x * inv, acc.y * inv);
-    w2[1] = pack_bf16(acc.z * inv, acc.w * inv);
+    w2[0] = pack_bf16(acc.x, acc.y);
+    w2[1] = pack_bf16(acc.z, acc.w);
     *(u32x2 *)out = w2;
     if (threadIdx.x == 0) p.lse[h] = (m_star + __builtin_amdgcn_logf(den)) * 0.69314718055994530942f;
 }
 
 // ---------------------------------------------------------------------------------------------------
-
-template <int DQK, int DV, bool ALIAS, bool PRECISE, bool OUTF32, bool EXT = false>
-static hipError_t launch_prefill_part(FwdParams p, int rt_begin, int rt_count, hipStream_t stream)
-{
-    if (rt_count <= 0) return hipSuccess;
-    using C = TileCfg<DQK, DV, 4, ALIAS, false, PRECISE>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, PRECISE, OUTF32, EXT>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    p.rt_begin = rt_begin;
-    p.row_tiles = rt_count;
-    const int64_t blocks = (int64_t)rt_count * p.Hkv * p.B;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
-    return hipGetLastError();
-}
 
 // A pattern that leaves rows beyond the first kPrecisePositions positions with fewer live keys than
 // that takes the two-term variant throughout. The smallest live set of such a row is at position
@@ -922,50 +996,54 @@ static bool pattern_needs_precise(const FwdParams &p)
     return live_at(kPrecisePositions - 1) < kPrecisePositions || (i0 < p.S && live_at(i0) < kPrecisePositions);
 }
 
-// leading row tiles (128 rows each) of a plain prefill that take the two-term variant
-static int precise_row_tiles(const FwdParams &p)
+// The tile kernels use more dynamic LDS than the default limit: raised once per kernel and device.
+template <auto KERN>
+static hipError_t allow_lds(int bytes)
 {
-    const int64_t prec_rows = (int64_t)(p.S < kPrecisePositions ? p.S : kPrecisePositions) * p.G;
-    int n_prec = (int)((prec_rows + 127) / 128);
-    if (n_prec > p.row_tiles || pattern_needs_precise(p)) n_prec = p.row_tiles;
-    return n_prec;
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute((const void *)KERN, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
+    return e;
+}
+
+template <int DQK, int DV, bool ALIAS, bool OUTF32, bool EXT>
+static hipError_t launch_prefill_kernel(FwdParams p, hipStream_t stream)
+{
+    using C = TileCfg<DQK, DV, 4, ALIAS, false>;
+    constexpr auto kern = ssa_fwd_kernel<DQK, DV, 4, ALIAS, false, OUTF32, EXT>;
+    hipError_t e = allow_lds<kern>(C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    p.rt_begin = 0;
+    p.all_precise = pattern_needs_precise(p) ? 1 : 0;
+    const int64_t blocks = (int64_t)p.row_tiles * p.Hkv * p.B;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
+    return hipGetLastError();
 }
 
 template <int DQK, int DV, bool ALIAS>
 static hipError_t launch_prefill_t(const FwdParams &p, hipStream_t stream)
 {
-    const int n_prec = precise_row_tiles(p);
-    // the long tiles first: the short precise ones fill the tail
-    if (p.out_f32 != nullptr) {
-        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, true>(p, n_prec, p.row_tiles - n_prec, stream);
-        if (e != hipSuccess) return e;
-        return launch_prefill_part<DQK, DV, ALIAS, true, true>(p, 0, n_prec, stream);
-    }
-    hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false>(p, n_prec, p.row_tiles - n_prec, stream);
-    if (e != hipSuccess) return e;
-    return launch_prefill_part<DQK, DV, ALIAS, true, false>(p, 0, n_prec, stream);
+    if (p.out_f32 != nullptr) return launch_prefill_kernel<DQK, DV, ALIAS, true, false>(p, stream);
+    return launch_prefill_kernel<DQK, DV, ALIAS, false, false>(p, stream);
 }
 
-// Extend prefill: which tiles lie among the first kPrecisePositions positions depends on the
-// sequence lengths on the device, so both variants run over all tiles and every tile exits from the
-// one it does not belong to.
+// Extend prefill: the same kernel in the form that takes its positions from the sequence lengths
 template <int DQK, int DV, bool ALIAS>
-static hipError_t launch_extend_t(FwdParams p, hipStream_t stream)
+static hipError_t launch_extend_t(const FwdParams &p, hipStream_t stream)
 {
-    p.all_precise = pattern_needs_precise(p) ? 1 : 0;
-    if (!p.all_precise) {
-        hipError_t e = launch_prefill_part<DQK, DV, ALIAS, false, false, true>(p, 0, p.row_tiles, stream);
-        if (e != hipSuccess) return e;
-    }
-    return launch_prefill_part<DQK, DV, ALIAS, true, false, true>(p, 0, p.row_tiles, stream);
+    return launch_prefill_kernel<DQK, DV, ALIAS, false, true>(p, stream);
 }
 
 template <int DQK, int DV, bool ALIAS>
 static hipError_t launch_decode_t(const FwdParams &p, hipStream_t stream)
 {
     using C = TileCfg<DQK, DV, 2, ALIAS, true>;
-    auto kern = ssa_fwd_kernel<DQK, DV, 2, ALIAS, true>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    constexpr auto kern = ssa_fwd_kernel<DQK, DV, 2, ALIAS, true>;
+    hipError_t e = allow_lds<kern>(C::LDS_BYTES);
     if (e != hipSuccess) return e;
     const int64_t blocks = (int64_t)p.n_splits * p.row_tiles * p.Hkv * p.B;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);

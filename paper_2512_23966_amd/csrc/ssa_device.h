@@ -71,10 +71,20 @@ __device__ __forceinline__ int window_begin_of(int i, int window, int block)
     return window > qb ? 0 : (qb - window + 1) * block;
 }
 
-// Positions below this take the two-term-P variant of the prefill kernel: with so few live keys
-// the output is as large as single value rows, and the bf16 rounding of P would be a visible share
-// of the error budget there. Beyond it every output averages enough keys for that to vanish.
+// Prefill tiles that start below this position are computed with two-term P (p = hi + lo, both
+// bf16) from the outset: with so few live keys the output is as large as single value rows, and the
+// bf16 rounding of P would be a visible share of the error budget there.
 constexpr int kPrecisePositions = 128;
+
+// Everywhere else the weights are rounded to bf16 once (relative error 2^-9 each), which reaches the
+// output as at most 2^-9 times the weighted mean distance of the value rows from the output. That is
+// harmless next to the output's own rounding while |out| < 2 (half an ulp of bf16 is at most 2^-8 there,
+// of a budget of 1e-2); from 2 on the rounding of the result alone takes 2^-7. Such results only come
+// from rows whose weight sits on a handful of keys, which is also where the rounding of P shows most:
+// a prefill tile that produced one (|out| >= this, a little below 2 so that the test cannot miss a
+// result just above it) is computed again with two-term P, and a decode query that did is computed
+// again by the merge kernel, directly in fp32.
+constexpr float kRedoMagnitude = 1.96875f;
 
 // A decode query with fewer live keys than this is not worth a matrix-core pass and, with so few
 // terms, would show the bf16 rounding of the softmax weights in its output: the split kernel leaves

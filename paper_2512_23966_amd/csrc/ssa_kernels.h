@@ -33,7 +33,7 @@ struct FwdParams {
     int rt_begin;      // first of them
     int n_splits;      // decode only
     int q_len;         // extend prefill: queries per sequence (0: plain prefill); keys valid up to seqlens[b]
-    int all_precise;   // extend prefill: every tile takes the two-term variant
+    int all_precise;   // prefill / extend: every tile takes the two-term pass (set by the launcher from the pattern)
     int exact_tiles;   // tiles over which the reference maximum is the exact running maximum
     float lazy_log2;   // afterwards it moves only when exceeded by this much (log2 units)
 };

@@ -112,6 +112,15 @@ def test_live_count_and_pair_closed_form(S, ns, W):
     assert oracle.count_pairs(S, ns, W) == closed
 
 
+@pytest.mark.parametrize("S,ns,W", [(50, 0, 1), (50, 3, 7), (64, 8, 16), (40, 64, 5), (33, 4, 1000), (300, 128, 100)])
+def test_closed_form_live_count_of_the_gpu_probes(S, ns, W):
+    """The closed form the full-size index-set probes compare every row's log-sum-exp with."""
+    from tests import helpers as H
+    i = np.arange(S, dtype=np.int64)
+    want = np.asarray([int(oracle.live_mask(int(x), S, ns, W).sum()) for x in i])
+    assert (H.live_count_tokens(i, ns, W) == want).all()
+
+
 def test_pair_counts_of_the_workloads():
     # closed form at the real sizes; the one-by-one count is checked at the smallest of them
     assert oracle.count_pairs(1024, 64, 256) == 276_640

@@ -69,6 +69,16 @@ def test_paper_sizes_give_at_most_1024_live_tokens():
     assert counts[2047] == 1024 and counts[2048] == 897
 
 
+@pytest.mark.parametrize("S,s,l,b", [(40, 1, 2, 4), (37, 0, 1, 5), (64, 2, 3, 8), (50, 1, 7, 128), (29, 3, 1, 2), (30, 1, 4, 1),
+                                     (1300, 1, 7, 128), (200, 3, 2, 16), (90, 5, 1, 8)])
+def test_closed_form_block_live_count_of_the_gpu_probes(S, s, l, b):
+    """The closed form the full-size index-set probe compares every row's log-sum-exp with."""
+    from tests import helpers as H
+    i = np.arange(S, dtype=np.int64)
+    want = np.asarray([int(oracle.live_mask_blocks(int(x), S, s, l, b).sum()) for x in i])
+    assert (H.live_count_blocks(i, s, l, b) == want).all()
+
+
 @pytest.mark.parametrize("S,s,l,b", [(40, 1, 2, 4), (37, 0, 1, 5), (64, 2, 3, 8), (50, 1, 7, 128), (29, 3, 1, 2), (30, 1, 4, 1)])
 def test_block_mask_equals_set_definition_and_pair_count(S, s, l, b):
     n = 0
