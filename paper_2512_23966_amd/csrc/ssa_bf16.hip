@@ -89,10 +89,12 @@ struct TileCfg {
     static constexpr int NSTAGE = DECODE ? 4 : 3;
     // copy instructions one wave issues per tile, at least (waves differ by at most one)
     static constexpr int MIN_COPIES = (K_INSTR - 2 * SC) / NCW + V_INSTR / NCW;
-    // A prefill tile can be (re)computed with P handed over as two bf16 terms (p = hi + lo), each with
-    // its own buffer pair; the decode's split kernel never does that (and has no room for it)
-    static constexpr int NPBUF = DECODE ? 2 : 4;
-    static constexpr int PLO = 2;                // index offset of the low-term buffers
+    // Two buffers for P. Rounded to bf16 once, the P of consecutive tiles alternate between them
+    // (the softmax of tile u + 1 writes one while the value phase of tile u reads the other). A
+    // two-term pass (p = hi + lo, both bf16) keeps hi in the first and lo in the second and pays for
+    // the missing double buffer with a second barrier per tile.
+    static constexpr int NPBUF = 2;
+    static constexpr int PLO = 1;                // index offset of the low-term buffer
     static constexpr int PROW = N * 2 + 16;      // LDS bytes per row of P (padded)
     static constexpr int PBYTES = M * PROW;
     static constexpr int OFF_P = NSTAGE * STAGE;
@@ -234,23 +236,20 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
     const int64_t seq_row0 = paged ? 0 : (int64_t)b * p.S;
     const char *kbase = (const char *)p.k + (seq_row0 * p.Hkv + g) * (int64_t)DQK * 2;
     const char *vbase = (const char *)p.v + (seq_row0 * p.Hkv + g) * (int64_t)DV * 2;
-    // The block-table entry of key tile t is fetched by a scalar load spelled out in asm (it must not
-    // count as a vector load: the tile loop waits on exact counts of those), in two steps so that
-    // the latency can be spent elsewhere: page_request() starts the load, page_wait() makes its
-    // result usable. Between the two nothing may read the value; page_wait() returns it.
+    // The block-table entry of key tile t is fetched by a scalar buffer load: it must not count as a
+    // vector load (the tile loop waits on exact counts of those), and it has to be a load the compiler
+    // knows about, so that the compiler places the wait before the first use of the value, however it
+    // moves the value between registers meanwhile. (A load spelled out in an asm statement, with the
+    // wait in a second statement, is not safe: the register may be copied between the two, before the
+    // data is there.) The tile loop asks for the entry one iteration ahead, so the latency is hidden.
+    // The buffer is this sequence's row of the table; an offset beyond it reads 0.
+    const i32x4 table_rsrc = paged ? table_row_resource(p.block_table + (int64_t)b * p.max_pages, p.max_pages) : i32x4{0, 0, 0, 0};
     auto page_request = [&](int t) -> int32_t {
-        int32_t pid = 0;
-        if (paged) {
-            const int64_t j0 = (int64_t)key_tile(t) * N;
-            const int32_t *e = p.block_table + ((int64_t)b * p.max_pages + (j0 >> p.page_shift));
-            asm volatile("s_load_dword %0, %1, 0x0" : "=s"(pid) : "s"(e) : "memory");
-        }
-        return pid;
+        if (!paged) return 0;
+        const int64_t j0 = (int64_t)key_tile(t) * N;
+        return llvm_amdgcn_s_buffer_load_i32(table_rsrc, (int32_t)((uint32_t)(j0 >> p.page_shift) * 4u), 0);
     };
-    auto page_wait = [&](int32_t pid) -> int32_t {
-        if (paged) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(pid) :: "memory");
-        return pid;
-    };
+    auto page_wait = [&](int32_t pid) -> int32_t { return pid; };
     // cache row (relative to kbase / vbase) at which key tile t starts, given its block-table entry
     auto tile_row = [&](int t, int32_t pid) -> int64_t {
         const int64_t j0 = (int64_t)key_tile(t) * N;
@@ -418,7 +417,7 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
         const bool rescale = __any(sm_up);
         if (lane == 0) s_flag[pbuf * 4 + wr] = rescale ? 1 : 0;
         if (rescale && lh == 0) s_alpha[pbuf * M + wr * 32 + ln] = sm_alpha;
-        char *pp = s_p + pbuf * C::PBYTES + (wr * 32 + ln) * C::PROW + (4 * lh) * 2;
+        char *pp = s_p + (PRECISE ? 0 : pbuf) * C::PBYTES + (wr * 32 + ln) * C::PROW + (4 * lh) * 2;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             u32x2 w;
@@ -527,7 +526,7 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
         const char *vtile = smem + stage * C::STAGE + (ALIAS ? 0 : C::KTILE);
         const int s16 = lane & 15, g16 = (lane >> 4) & 1;
         vp = vtile + (lh * 8 + (s16 >> 2)) * C::VROW + (vw * C::DVW + g16 * 16 + (s16 & 3) * 4) * 2;
-        pb = s_p + pbuf * C::PBYTES + ln * C::PROW + lh * 16;
+        pb = s_p + (PRECISE ? 0 : pbuf) * C::PBYTES + ln * C::PROW + lh * 16;
     };
     auto load_v = [&](const char *vp, int step, s16x4 &lo, s16x4 &hi) {
         const char *va = vp + (step / C::DVB) * 16 * C::VROW + (step % C::DVB) * 64;
@@ -581,7 +580,8 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
                 if (WITH_SOFTMAX) {
 #pragma unroll
                     for (int jj = 0; jj < JPS; ++jj)
-                        if (slot * JPS + jj < SM_JOBS) sm_job(std::true_type{}, slot * JPS + jj, s, j0_next, lazy, pbuf_next);
+                        // (two-term pass: the hand-over, the last job, waits for a barrier of its own)
+                        if (slot * JPS + jj < SM_JOBS - (PRECISE ? 1 : 0)) sm_job(std::true_type{}, slot * JPS + jj, s, j0_next, lazy, pbuf_next);
                 }
                 after_slot(slot, NSLOT);
                 __builtin_amdgcn_sched_barrier(0);
@@ -659,6 +659,11 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
             rescale_tile(u & 1, flags);
             value_tile(st_v, u & 1, vf, std::true_type{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff,
                        (u + 1) & 1, u + 1 < p.exact_tiles ? 0.f : p.lazy_log2, [](int, int) {});
+            if constexpr (PRECISE) {
+                // every wave has read P of tile u: the single pair of buffers can take P of tile u + 1
+                lds_barrier();
+                sm_end_fn((u + 1) & 1);
+            }
             st_v = st_k;
         }
     } else if (scorer) {

@@ -14,10 +14,28 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((address_space(1))) const void *glb_void_ptr;
 
 #define LOZA_NEG_INF (-__builtin_inff())
+
+// Scalar (wave-uniform) load of one dword through a buffer resource: the LLVM intrinsic behind
+// s_buffer_load_dword. The compiler tracks it like any other load (it waits before the first use).
+__device__ int32_t llvm_amdgcn_s_buffer_load_i32(i32x4 rsrc, int32_t byte_offset, int32_t cachepolicy) __asm("llvm.amdgcn.s.buffer.load.i32");
+
+// Buffer resource (gfx9 layout) over `entries` consecutive int32 values at `base`: raw buffer, no
+// stride, the size in bytes as its range (reads beyond it return 0), 32-bit data format.
+static __device__ __forceinline__ i32x4 table_row_resource(const int32_t *base, int entries)
+{
+    const uint64_t a = (uint64_t)base;
+    i32x4 r;
+    r[0] = (int32_t)(uint32_t)a;
+    r[1] = (int32_t)((uint32_t)(a >> 32) & 0xffffu);
+    r[2] = entries * 4;
+    r[3] = 0x00020000;
+    return r;
+}
 
 static __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 {

@@ -134,7 +134,10 @@ def test_paged_decode_at_the_benchmark_shape(gpu_device):
         a_, c_ = b * max_pages + last, b * max_pages + last - 1
         tmp = pool[a_].clone(); pool[a_] = pool[c_]; pool[c_] = tmp
     out_c, lse_c = H.run_decode(q, kc, vc, seqlens, cfg.n_sink, cfg.window, cfg.scale, d_v=cfg.d_v)
-    assert torch.equal(out_p.view(torch.int16), out_c.view(torch.int16))
+    diff = (out_p.view(torch.int16) != out_c.view(torch.int16)).nonzero()
+    assert diff.numel() == 0, (f"paged and contiguous decode differ in {diff.shape[0]} elements; sequences "
+                               f"{sorted(set(diff[:, 0].tolist()))[:8]}, heads {sorted(set(diff[:, 1].tolist()))[:8]}, columns "
+                               f"{sorted(set(diff[:, 2].tolist()))[:8]}; max |difference| {(out_p.float() - out_c.float()).abs().max().item():.3e}")
     assert torch.equal(lse_p.view(torch.int32), lse_c.view(torch.int32))
     heads = np.asarray([0, 31, 63], dtype=np.int64)
     rb = np.repeat(np.arange(cfg.B, dtype=np.int64), len(heads))
