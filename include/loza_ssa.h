@@ -14,7 +14,7 @@
  *
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers unless stated; the caller owns every buffer; the
- *     library allocates nothing, keeps no state between calls and performs no host sync.
+ *     library allocates nothing and performs no host sync. It keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls are
  *     asynchronous on it.
  *   - Layouts are dense, innermost index fastest. bf16 tensors are raw 16-bit patterns.
@@ -24,6 +24,14 @@
  *   - Base pointers must be 16-byte aligned. Inputs must be finite.
  *   - Every argument is validated before the first HIP call; a failed validation launches nothing.
  *   - Return value: LOZA_OK or a negative loza_status.
+ *   - One environment variable is read (on every decode call and by the two host-only size functions
+ *     below): LOZA_DECODE_SPLITS=n, 1 <= n <= 64, replaces the number of key splits a decode call
+ *     chooses from its sizes (other values are ignored). It exists for tests and experiments; it
+ *     changes the workspace size, so it must not change between loza_ssa_decode_workspace_bytes and
+ *     the decode call. Nothing else is read from the environment.
+ *   - Where each declaration comes from: the prototypes of loza_ssa_prefill and loza_ssa_decode are
+ *     given by the benchmark spec; the operation is the paper's (cited at each entry point); every
+ *     other name, argument and helper is this library's own.
  */
 #ifndef LOZA_SSA_H
 #define LOZA_SSA_H
@@ -57,9 +65,18 @@ typedef enum {
  * Supported (d_qk, d_v): (576, 512) with v == k (absorbed MLA: the value row is the first 512
  * elements of the key row), and (128, 128) with v separate or v == k. Anything else:
  * LOZA_ERR_UNSUPPORTED. S <= 2^31 - 129.
- * Numerics: scores and sums in fp32, the softmax weights rounded to bf16 for the value product
- * (to two bf16 terms for the first 128 positions, whose few-key rows would otherwise carry the
- * weight rounding into the output undamped); |out - exact| <= 1e-2 for |out| <= 4.
+ * Numerics: scores, exponentials and sums in fp32; the softmax weights go to the matrix cores as
+ * bf16, rounded once (relative error 2^-9 each) or, where that is not good enough, as two bf16
+ * terms (2^-17): for tiles that start within the first 128 positions, for patterns that leave every
+ * row fewer than 128 live keys, and for every tile in which the one-term pass produced a result of
+ * magnitude >= 1.97 (the tile is then computed again inside the same launch). Error of a result:
+ *     |out - exact| <= half an ulp of bf16 at |out|  +  w * D  +  about 1e-6 * |out|,
+ * D = the softmax-weighted mean of |v_j - out| over the live keys (never more than their largest
+ * distance from out), w = 2^-9 for one-term rows and 2^-17 for two-term rows. One-term rows have
+ * |out| < 2, i.e. half an ulp <= 2^-8: they stay inside 1e-2 whenever D <= 3.1 (values of unit
+ * scale give D of about 1, and random rounding errors add to a small fraction of w * D); two-term
+ * rows stay inside 1e-2 for |out| < 4 whenever D <= 280. From |out| = 4 on the rounding of the
+ * result to bf16 alone is 2^-6. lse: fp32 throughout, |lse - exact| <= 2e-5 at the tested sizes.
  * The launch is deterministic: the same inputs give the same bits.
  */
 int loza_ssa_prefill(const void *q, const void *k, const void *v, void *out, float *lse,
@@ -89,19 +106,23 @@ int loza_ssa_prefill_f32(const float *q, const float *k, const float *v, float *
  *           head, key split), the unnormalised fp32 partial output and four floats of softmax
  *           state. Two calls that overlap in time need two workspaces.
  * Supported (d_qk, d_v) and scale: as loza_ssa_prefill. Cache rows at or beyond seqlens[b] are
- * never read. The split count depends on the sizes only, and the merge adds the splits in a
- * fixed order: the result is deterministic.
+ * never read. The split count depends on the sizes only (and on LOZA_DECODE_SPLITS, see above), and
+ * the merge adds the splits in a fixed order: the result is deterministic.
+ * Numerics: as loza_ssa_prefill with one-term weights, except that a query with fewer than 128
+ * live keys, and a query whose merged result reaches magnitude 1.97 in some column, is computed
+ * from the cache rows directly in fp32 (weights not rounded at all; a rare, slower path: one
+ * workgroup walks all live keys of that query).
  */
 int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
                     void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
                     int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
                     void *workspace, size_t workspace_bytes, void *stream);
 
-/* Host-only. Bytes of workspace loza_ssa_decode needs for these sizes (0 on invalid sizes). */
+/* Host-only (ours). Bytes of workspace loza_ssa_decode needs for these sizes (0 on invalid sizes). */
 size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, int d_v,
                                        int64_t n_sink, int64_t window);
 
-/* Host-only. Number of key splits loza_ssa_decode uses for these sizes (0 on invalid sizes). */
+/* Host-only (ours). Number of key splits loza_ssa_decode uses for these sizes (0 on invalid sizes). */
 int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_sink, int64_t window);
 
 /*
@@ -113,7 +134,9 @@ int loza_ssa_decode_num_splits(int B, int Hq, int Hkv, int64_t S_max, int64_t n_
 int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
                          int64_t *sink_end, int64_t *win_begin, int64_t *win_end);
 
-/* Host-only. Live (query, key) pairs of a causal length-S prefill: sum over i of |live(i)|. */
+/* Host-only (ours). Live (query, key) pairs of a causal length-S prefill: the sum over i of |live(i)|
+ * for the live sets of Eq. 4 as defined at the top of this file. This is the pair count the
+ * benchmark's FLOP figure is built on ("compute per query stays constant": Architecture section). */
 int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window);
 
 /*
@@ -233,7 +256,7 @@ int loza_ssa_prefill_calibration_blocks(const void *q, const void *k, const void
                                         int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                         float alpha, float scale, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Host-only. Workspace bytes of loza_ssa_prefill_calibration_blocks (0 on invalid sizes). */
+/* Host-only (ours). Workspace bytes of loza_ssa_prefill_calibration_blocks (0 on invalid sizes). */
 size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v);
 
 /*
@@ -242,8 +265,8 @@ size_t loza_ssa_calibration_workspace_bytes(int B, int Hq, int64_t S, int d_v);
  *   dout, out_full, out_sparse: n bf16 elements each (device, 16-byte aligned): the gradient arriving
  *       at the blend and the two outputs loza_ssa_prefill_calibration_blocks wrote; n >= 8, a multiple of 8
  *   dalpha: one float on the device (overwritten)
- *   workspace: loza_ssa_calibration_alpha_grad_workspace_bytes(n) bytes of device memory (0 for an n the
- *       call rejects), 16-byte aligned, contents ignored
+ *   workspace: loza_ssa_calibration_alpha_grad_workspace_bytes(n) bytes of device memory (host-only
+ *       helper, ours; 0 for an n the call rejects), 16-byte aligned, contents ignored
  * Products and sums in fp64 in a fixed order (deterministic), one rounding to fp32 at the end.
  */
 int loza_ssa_calibration_alpha_grad(const void *dout, const void *out_full, const void *out_sparse, float *dalpha, int64_t n,
@@ -317,7 +340,7 @@ int loza_ssa_backward_blocks_f32(const float *q, const float *k, const float *v,
                                  int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                                  int64_t sink_blocks, int64_t local_blocks, int64_t block, float scale, void *stream);
 
-/* Host-only. Workspace bytes of loza_ssa_backward / loza_ssa_backward_blocks for these sizes
+/* Host-only (ours). Workspace bytes of loza_ssa_backward / loza_ssa_backward_blocks for these sizes
  * (v_aliases_k: nonzero when v == k will be passed); 0 on sizes the call would reject. */
 size_t loza_ssa_backward_workspace_bytes(int B, int Hq, int Hkv, int64_t S, int d_qk, int d_v,
                                          int64_t n_sink, int64_t window, int v_aliases_k);
@@ -325,12 +348,13 @@ size_t loza_ssa_backward_workspace_bytes_blocks(int B, int Hq, int Hkv, int64_t 
                                                 int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                                 int v_aliases_k);
 
-/* Host-only twins of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern. */
+/* Host-only twins (ours) of loza_ssa_live_ranges / loza_ssa_live_pairs for the block-granular pattern
+ * (Architecture section after Eq. 4: sink blocks, local blocks, block size). */
 int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_blocks, int64_t block,
                                 int64_t *sink_end, int64_t *win_begin, int64_t *win_end);
 int64_t loza_ssa_live_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block);
 
-/* Host-only. Static string naming a status code. */
+/* Host-only (ours). Static string naming a status code. */
 const char *loza_status_str(int status);
 
 #ifdef __cplusplus

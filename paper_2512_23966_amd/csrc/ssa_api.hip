@@ -106,7 +106,7 @@ int loza_ssa_live_ranges(int64_t i, int64_t n_sink, int64_t window,
                          int64_t *sink_end, int64_t *win_begin, int64_t *win_end)
 {
     if (!sink_end || !win_begin || !win_end) return LOZA_ERR_NULL;
-    if (i < 0 || n_sink < 0 || window < 1) return LOZA_ERR_SHAPE;
+    if (i < 0 || i == INT64_MAX || n_sink < 0 || window < 1) return LOZA_ERR_SHAPE;  // i + 1 is returned
     const int64_t se = n_sink < i + 1 ? n_sink : i + 1;
     int64_t wb = window > i ? 0 : i - window + 1;
     if (wb < se) wb = se;  // a key in both sets is used once
@@ -120,7 +120,7 @@ int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_bl
                                 int64_t *sink_end, int64_t *win_begin, int64_t *win_end)
 {
     if (!sink_end || !win_begin || !win_end) return LOZA_ERR_NULL;
-    if (i < 0 || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return LOZA_ERR_SHAPE;
+    if (i < 0 || i == INT64_MAX || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return LOZA_ERR_SHAPE;
     const int64_t sink_tokens = sat_mul(sink_blocks, block);
     const int64_t se = sink_tokens < i + 1 ? sink_tokens : i + 1;
     const int64_t qb = i / block;
@@ -134,9 +134,10 @@ int loza_ssa_live_ranges_blocks(int64_t i, int64_t sink_blocks, int64_t local_bl
 
 int64_t loza_ssa_live_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local_blocks, int64_t block)
 {
-    if (S < 1 || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return -1;
+    if (S < 1 || S > kMaxSeq || check_blocks(sink_blocks, local_blocks, block) != LOZA_OK) return -1;
     // query block by query block: inside one block the window start is fixed and |live(i)| grows by one
     const int64_t sink_tokens = sat_mul(sink_blocks, block);
+    if (block > S) block = S;  // one block already holds every position (and i0 + block cannot overflow)
     int64_t pairs = 0;
     for (int64_t i0 = 0; i0 < S; i0 += block) {
         const int64_t i1 = (i0 + block < S ? i0 + block : S) - 1;  // last query of the block
@@ -154,7 +155,7 @@ int64_t loza_ssa_live_pairs_blocks(int64_t S, int64_t sink_blocks, int64_t local
 
 int64_t loza_ssa_live_pairs(int64_t S, int64_t n_sink, int64_t window)
 {
-    if (S < 1 || n_sink < 0 || window < 1) return -1;
+    if (S < 1 || S > kMaxSeq || n_sink < 0 || window < 1) return -1;
     // |live(i)| = min(i + 1, T), T = n_sink + window (saturating)
     const int64_t T = (window >= S || n_sink >= S || n_sink + window >= S) ? S : n_sink + window;
     return T * (T + 1) / 2 + (S - T) * T;

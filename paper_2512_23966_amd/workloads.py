@@ -35,19 +35,6 @@ class PrefillConfig:
     scale: float
     seed: int
 
-    @property
-    def live_per_query(self) -> int:
-        w = self.S if self.window is None else min(self.window, self.S)
-        return min(self.S, self.n_sink + w)
-
-    def live_pairs(self) -> int:
-        T, S = self.live_per_query, self.S
-        return T * (T + 1) // 2 + (S - T) * T
-
-    def flops(self) -> float:
-        """Counted FLOP: 2 * (d_qk + d_v) per live (query, key, head) pair."""
-        return 2.0 * self.live_pairs() * (self.d_qk + self.d_v) * self.Hq * self.B
-
 
 @dataclass(frozen=True)
 class DecodeConfig:
