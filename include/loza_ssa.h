@@ -14,7 +14,8 @@
  *
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers unless stated; the caller owns every buffer; the
- *     library allocates nothing and performs no host sync. It keeps no state between calls.
+ *     library allocates nothing and performs no host sync. It keeps no state between calls (the one
+ *     exception, a scratch buffer whose contents never matter, is described at loza_ssa_decode_static).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls are
  *     asynchronous on it.
  *   - Layouts are dense, innermost index fastest. bf16 tensors are raw 16-bit patterns.
@@ -117,6 +118,25 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
                     void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
                     int d_qk, int d_v, int64_t n_sink, int64_t window, float scale,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * loza_ssa_decode for callers that cannot allocate device memory or carry a workspace around (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels,
+ * the same result bits, with the partial results of the key splits in a buffer that is part of the
+ * library image (LOZA_DECODE_STATIC_BYTES of device memory on every GPU the library is used on, held
+ * until the process ends). No hipMalloc / hipFree, here or in anything it calls.
+ *   - sizes whose workspace (loza_ssa_decode_workspace_bytes) exceeds LOZA_DECODE_STATIC_BYTES are
+ *     rejected with LOZA_ERR_WORKSPACE before anything is launched; LOZA_DECODE_STATIC_BYTES covers
+ *     B * Hq * splits <= 20,321 at d_v = 512 (B = 64 sequences of 64 heads in 4 splits use 16,384).
+ *   - every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it and must be serialised by the caller. Nothing in it has to
+ *     survive or be cleared between calls.
+ * All other arguments, errors and numerics: as loza_ssa_decode.
+ */
+#define LOZA_DECODE_STATIC_BYTES (40u << 20)
+int loza_ssa_decode_static(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                           void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                           int d_qk, int d_v, int64_t n_sink, int64_t window, float scale, void *stream);
 
 /* Host-only (ours). Bytes of workspace loza_ssa_decode needs for these sizes (0 on invalid sizes). */
 size_t loza_ssa_decode_workspace_bytes(int B, int Hq, int Hkv, int64_t S_max, int d_v,

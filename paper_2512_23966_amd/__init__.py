@@ -18,4 +18,5 @@ from .binding import (  # noqa: F401
     loza_ssa_backward_f32, loza_ssa_backward_blocks_f32,
     loza_ssa_decode_f32, loza_ssa_decode_blocks_f32,
     loza_ssa_calibration_alpha_grad, loza_ssa_calibration_alpha_grad_workspace_bytes,
+    loza_ssa_decode_static, LOZA_DECODE_STATIC_BYTES,
 )

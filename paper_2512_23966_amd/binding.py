@@ -34,6 +34,7 @@ EXPORTS = (
     "loza_ssa_backward_f32", "loza_ssa_backward_blocks_f32",
     "loza_ssa_decode_f32", "loza_ssa_decode_blocks_f32",
     "loza_ssa_calibration_alpha_grad", "loza_ssa_calibration_alpha_grad_workspace_bytes",
+    "loza_ssa_decode_static",
 )
 
 
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.loza_ssa_prefill_f32.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_decode.restype = ci
         L.loza_ssa_decode.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp, sz, vp]
+        L.loza_ssa_decode_static.restype = ci
+        L.loza_ssa_decode_static.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, i64, ci, ci, i64, i64, f32, vp]
         L.loza_ssa_decode_workspace_bytes.restype = sz
         L.loza_ssa_decode_workspace_bytes.argtypes = [ci, ci, ci, i64, ci, i64, i64]
         L.loza_ssa_decode_num_splits.restype = ci
@@ -244,6 +247,29 @@ def loza_ssa_decode(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale,
     """bf16 SSA decode (token-granular pattern); tensors as in :func:`_decode_common`."""
     _decode_common("loza_ssa_decode", q, kcache, vcache, seqlens, out, lse, (int(n_sink), _win(window)), scale,
                    workspace, stream)
+
+
+LOZA_DECODE_STATIC_BYTES = 40 << 20
+
+
+def loza_ssa_decode_static(q, kcache, vcache, seqlens, out, lse, n_sink, window, scale, stream=None):
+    """:func:`loza_ssa_decode` without a workspace argument: the library's own static device buffer
+    holds the partial results (sizes beyond ``LOZA_DECODE_STATIC_BYTES`` are rejected)."""
+    B, Hq, d_qk = q.shape
+    _, S_max, Hkv, _ = kcache.shape
+    d_v = out.shape[2]
+    if kcache.shape != (B, S_max, Hkv, d_qk) or out.shape != (B, Hq, d_v) or lse.shape != (B, Hq) or seqlens.shape != (B,):
+        raise ValueError("shape mismatch between q, kcache, seqlens, out, lse")
+    if vcache is not kcache and vcache.shape != (B, S_max, Hkv, d_v):
+        raise ValueError("vcache must be [B, S_max, Hkv, d_v] (or the very tensor passed as kcache)")
+    bf = torch.bfloat16
+    qp, kp = _dev_ptr(q, bf, "q"), _dev_ptr(kcache, bf, "kcache")
+    vp = kp if vcache is kcache else _dev_ptr(vcache, bf, "vcache")
+    rc = lib().loza_ssa_decode_static(qp, kp, vp, _dev_ptr(seqlens, torch.int32, "seqlens"), _dev_ptr(out, bf, "out"),
+                                      _dev_ptr(lse, torch.float32, "lse"), B, Hq, Hkv, S_max, d_qk, d_v,
+                                      int(n_sink), _win(window), float(scale), _stream(stream))
+    if rc != LOZA_OK:
+        raise LozaError(rc, "loza_ssa_decode_static")
 
 
 def loza_ssa_decode_blocks(q, kcache, vcache, seqlens, out, lse, sink_blocks, local_blocks, block, scale, workspace,

@@ -5,10 +5,36 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "../../include/loza_ssa.h"
 #include "ssa_kernels.h"
 
+// Scratch memory of loza_ssa_decode_static: the split kernel's partial results, in the place of a
+// caller's workspace. One copy per GPU, at an address of its own on each; the name below is only a
+// host-side handle for hipGetSymbolAddress and is never passed to a kernel.
+static __device__ __align__(256) unsigned char scratch[LOZA_DECODE_STATIC_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices];      // device address of `scratch` on device d (nullptr: not asked yet)
+
+// Device address of the scratch array on the current device (asked once per device, then kept).
+int scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LOZA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[dev] == nullptr) {
+        void *a = nullptr;
+        if (hipGetSymbolAddress(&a, HIP_SYMBOL(scratch)) != hipSuccess || a == nullptr) return LOZA_ERR_HIP;
+        scratch_ptr[dev] = a;
+    }
+    *ptr = scratch_ptr[dev];
+    return LOZA_OK;
+}
 
 constexpr int kComputeUnits = 256;              // MI355X
 constexpr int64_t kMaxSeq = 2147483647LL - 128;  // positions are 32-bit inside the kernels
@@ -656,6 +682,21 @@ int loza_ssa_decode(const void *q, const void *kcache, const void *vcache, const
 {
     return decode_bf16(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false,
                        scale, workspace, workspace_bytes, stream);
+}
+
+int loza_ssa_decode_static(const void *q, const void *kcache, const void *vcache, const int32_t *seqlens,
+                           void *out, float *lse, int B, int Hq, int Hkv, int64_t S_max,
+                           int d_qk, int d_v, int64_t n_sink, int64_t window, float scale, void *stream)
+{
+    // sizes first (no HIP call on a rejected size), then the per-device address of the scratch array
+    if (check_common(B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, scale) != LOZA_OK) return LOZA_ERR_SHAPE;
+    const size_t need = loza_ssa_decode_workspace_bytes(B, Hq, Hkv, S_max, d_v, n_sink, window);
+    if (need == 0) return LOZA_ERR_SHAPE;
+    if (need > (size_t)LOZA_DECODE_STATIC_BYTES) return LOZA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (int rc = scratch_of_current_device(&ws)) return rc;
+    return decode_bf16(q, kcache, vcache, seqlens, out, lse, B, Hq, Hkv, S_max, d_qk, d_v, n_sink, window, 1, false,
+                       scale, ws, (size_t)LOZA_DECODE_STATIC_BYTES, stream);
 }
 
 int loza_ssa_decode_paged(const void *q, const void *k_pages, const void *v_pages, const int32_t *block_table,

@@ -35,13 +35,14 @@ int main(void)
     /* validation of the launching entry points: everything below is rejected before any device call */
     char buf[64];
     void *p = (void *)(((uintptr_t)buf + 15) & ~(uintptr_t)15);
-    printf("rejected %d %d %d %d %d %d\n",
+    printf("rejected %d %d %d %d %d %d %d\n",
            loza_ssa_prefill(NULL, p, p, p, (float *)p, 1, 1, 1, 16, 128, 128, 0, 1, 1.0f, NULL),
            loza_ssa_prefill(p, p, p, p, (float *)p, 1, 3, 2, 16, 128, 128, 0, 1, 1.0f, NULL),
            loza_ssa_prefill(p, p, p, p, (float *)p, 1, 1, 1, INT64_MAX, 128, 128, 0, 1, 1.0f, NULL),
            loza_ssa_prefill(p, p, p, p, (float *)p, 1, 1, 1, 16, 96, 64, 0, 1, 1.0f, NULL),
            loza_ssa_prefill((char *)p + 2, p, p, p, (float *)p, 1, 1, 1, 16, 128, 128, 0, 1, 1.0f, NULL),
-           loza_ssa_decode(p, p, p, (const int32_t *)p, p, (float *)p, 64, 64, 1, 262144, 576, 512, INT64_MAX, INT64_MAX, 0.07f, p, 16, NULL));
+           loza_ssa_decode(p, p, p, (const int32_t *)p, p, (float *)p, 64, 64, 1, 262144, 576, 512, INT64_MAX, INT64_MAX, 0.07f, p, 16, NULL),
+           loza_ssa_decode_static(p, p, p, (const int32_t *)p, p, (float *)p, 1000, 64, 1, 262144, 576, 512, 128, 8192, 0.07f, NULL));
     printf("status %s\n", loza_status_str(LOZA_ERR_ALIGN));
     return 0;
 }

@@ -111,5 +111,5 @@ def test_library_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_
     assert got["edges"] == [str(acc)]
     assert got["calibration_ws"] == [str(B.loza_ssa_calibration_workspace_bytes(1, 64, 4096, 512)), "0"]
     assert got["alpha_grad_ws"][0] == str(B.loza_ssa_calibration_alpha_grad_workspace_bytes(4096))
-    assert got["rejected"] == ["-1", "-2", "-2", "-3", "-6", "-4"]
+    assert got["rejected"] == ["-1", "-2", "-2", "-3", "-6", "-4", "-4"]
     assert " ".join(got["status"]) == B.loza_status_str(-6)
