@@ -37,6 +37,9 @@ def main() -> int:
     ap.add_argument("--no-backward", action="store_true", help="skip the backward of the timed prefill")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the untimed-region extras: the 32K MHA and the 1M-token MLA prefill configurations")
+    ap.add_argument("--only", choices=["cfg2"], default=None,
+                    help="profiling aid: launch just this workload --steps times (after --warmup untimed launches) "
+                         "and print its time; cfg2 = the 32K-token MHA prefill (d = 128)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (what HBM byte counters "
                          "collected with rocprofv3 --pmc are scaled by)")
@@ -57,6 +60,29 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     pc, dc = W.CFG3, W.CFG4
+
+    if args.only == "cfg2":
+        cfg = W.CFG2
+        q2, k2, v2 = W.make_prefill_inputs(cfg, dev)
+        o2 = torch.empty(cfg.B, cfg.S, cfg.Hq, cfg.d_v, dtype=cfg.dtype, device=dev)
+        l2 = torch.empty(cfg.B, cfg.Hq, cfg.S, dtype=torch.float32, device=dev)
+        for _ in range(args.warmup):
+            loza.loza_ssa_prefill(q2, k2, v2, o2, l2, cfg.n_sink, cfg.window, cfg.scale)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            loza.loza_ssa_prefill(q2, k2, v2, o2, l2, cfg.n_sink, cfg.window, cfg.scale)
+        b.record(); torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        flop = 2.0 * loza.loza_ssa_live_pairs(cfg.S, cfg.n_sink, cfg.window) * (cfg.d_qk + cfg.d_v) * cfg.Hq * cfg.B
+        if args.copy_calibration:
+            src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+            dst = torch.empty_like(src)
+            torch.neg(src, out=dst)
+            torch.cuda.synchronize()
+        print(json.dumps({"only": cfg.name, "steps": args.steps, "prefill_ms": round(ms, 4), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+                          "mfma_frac": round(flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}))
+        return 0
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
     q, k, v = W.make_prefill_inputs(pc, dev)
@@ -178,6 +204,25 @@ def main() -> int:
             "decode_us": round(full_decode_ms * 1e3, 1), "decode_speedup": round(full_decode_ms / decode_ms, 2),
             "decode_gbps": round((float(seqlens_host.sum()) * dc.d_qk * 2) / (full_decode_ms * 1e-3) / 1e9, 1),
         }
+
+    # ---- calibration forward (Eq. 3: alpha * full + (1 - alpha) * sparse) of the timed prefill --------------
+    if not args.no_comparator:
+        free, _ = torch.cuda.mem_get_info()
+        cal_bytes = loza.loza_ssa_calibration_workspace_bytes(pc.B, pc.Hq, pc.S, pc.d_v)
+        if free > cal_bytes + 3 * out.numel() * 2 + (8 << 30):
+            ws_cal = torch.empty(cal_bytes, dtype=torch.uint8, device=dev)
+            o_mix, o_full, o_sparse = torch.empty_like(out), torch.empty_like(out), torch.empty_like(out)
+            lse_f = torch.empty_like(lse)
+            # block = 1: the token-granular pattern of the timed prefill (sink_blocks = n_sink, local_blocks = window)
+            cal_ms = timed(lambda: loza.loza_ssa_prefill_calibration_blocks(
+                q, k, v, o_mix, o_full, o_sparse, lse_f, lse, pc.n_sink, pc.window, 1, 0.5, pc.scale, ws_cal), 1)
+            result["calibration_forward"] = {
+                "workload": "Eq. 3 on the timed prefill's tensors: full-attention pass + sparse pass + blend (all three outputs written)",
+                "ms": round(cal_ms, 2), "times_full_attention": round(cal_ms / full_prefill_ms, 3),
+                "times_sparse_prefill": round(cal_ms / prefill_ms, 2),
+            }
+            del ws_cal, o_mix, o_full, o_sparse, lse_f
+            torch.cuda.empty_cache()
 
     # ---- the paper's own parametrisation on the same tensors: 1 sink block + 7 local blocks of 128 ----
     if not args.no_comparator:

@@ -202,16 +202,14 @@ def run_backward_f32(q, k, v, out, lse, dout, n_sink, window, scale, block=None)
     return dq, dk, dv
 
 
-# fp32 arithmetic throughout: dot products of up to 256 terms, expf of an argument of size ~10 (its
-# rounding alone is 1e-6 relative in the weight), sums over up to thousands of terms of mixed sign.
-# Bound per element: 4e-5 of the rms of its row (the size of the terms that were summed), 1e-5 of
-# the element, and a floor of 1e-5 for rows that vanish by cancellation: a query with one live key has
-# dP = D exactly, the kernel forms both as fp32 dot products of up to 256 terms of size ~1 in
-# different orders (difference ~ 2^-23 * sqrt(256) * |dO||v| ~ 4e-6), and that difference times
+# fp32 arithmetic throughout: the task's bound for the fp32 path, 1e-5, flat, plus 1e-5 of the element
+# for gradients larger than one (fp32 holds 7 digits: an element of size 30 cannot be good to 1e-5).
+# Measured: <= 6e-6. The flat part also covers the rows that vanish by cancellation: a query with one
+# live key has dP = D exactly, the kernel forms both as fp32 dot products of up to 256 terms of size ~1
+# in different orders (difference ~ 2^-23 * sqrt(256) * |dO||v| ~ 4e-6), and that difference times
 # scale * |k| is what its dq row holds instead of zero.
 def grad_tolerance_f32(ref: np.ndarray) -> np.ndarray:
-    row_rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
-    return 4e-5 * row_rms + 1e-5 * np.abs(ref) + 1e-5
+    return 1e-5 + 1e-5 * np.abs(ref)
 
 
 def compare_backward_f32(q, k, v, out, lse, dout, got, n_sink, window, scale, label="", block=None):
@@ -261,11 +259,18 @@ def run_backward(q, k, v, out, lse, dout, n_sink, window, scale, block=None):
 # random sign), so its error is a random sum of the same size as 2^-9 times the root-sum-square of
 # the terms -- which is also the typical size of the elements of that row, whether or not the
 # element itself happens to be small by cancellation. The bound is therefore GRAD_K of those units
-# (rms of the reference row times 2^-9), GRAD_K covering the several rounded factors (p, dS, the
-# bf16 `out` inside D) and the maximum over millions of elements, plus the rounding of the result,
-# plus a floor for rows whose gradient vanishes by cancellation (a query with one live key has
-# dP = D exactly; the kernel forms the two 512-term dot products in fp32 in different orders).
-GRAD_K = 16.0
+# (rms of the reference row times 2^-9), plus the rounding of the result, plus a floor for rows whose
+# gradient vanishes by cancellation (a query with one live key has dP = D exactly; the kernel forms
+# the two 512-term dot products in fp32 in different orders).
+# GRAD_K: one rounded factor per term gives an error of standard deviation 0.58 units (uniform
+# rounding error of relative half-width 2^-9 against terms whose root-sum-square is the row's rms x
+# sqrt(width)); a term of dK or dQ carries two rounded factors (p inside dS, and dS itself) and the
+# rounded `out` inside D shifts every dS of a row together: ~1.2 units of standard deviation where the
+# row is dominated by few keys. The maximum over the 10^7 .. 10^8 elements of a test sits 5.5 to 6
+# standard deviations out, i.e. at 7 units; measured over every case of the suite: 6 .. 11.4 (the
+# high end on rows whose weight sits on one or two keys, where the errors of a row do not average).
+# 13 leaves 15 % over the largest value seen.
+GRAD_K = 13.0
 GRAD_FLOOR = 2e-5
 
 
