@@ -66,6 +66,22 @@ def test_d128_backward(gpu_device, B, S, Hq, Hkv, alias, ns, win, block):
                        f"d128 bwd B{B} S{S} Hq{Hq} Hkv{Hkv} alias{alias} ns{ns} W{win} b{block}", block)
 
 
+def test_mla_backward_dense_gradient_over_several_sink_chunks(gpu_device):
+    """Every row contributes (dense dO) at a length where a key tile with sink keys is seen by several
+    chunks of rows (their fp32 partial tiles are summed by the reduce kernel) and the key tiles of a
+    window are many: S = 2048, 64 heads on one latent, 128 sink tokens, window 512."""
+    import paper_2512_23966_amd as loza
+    B, S, Hq, ns, win = 1, 2048, 64, 128, 512
+    q, k, v, dout = _case(gpu_device, B, S, Hq, 1, 576, 512, alias=True, seed=50)
+    scale = 192 ** -0.5
+    # the schedule really has more than one chunk per sink tile: the workspace holds their partial tiles
+    stat_only = B * 1 * ((S * Hq + 31) // 32 * 32) * 8
+    assert loza.loza_ssa_backward_workspace_bytes(B, Hq, 1, S, 576, 512, ns, win, True) > stat_only + 2 * 64 * 576 * 4
+    out, lse = H.oracle_forward_all(q, k, v, ns, win, scale, 512)
+    got = H.run_backward(q, k, v, out, lse, dout, ns, win, scale)
+    H.compare_backward(q, k, v, out, lse, dout, got, ns, win, scale, f"mla bwd dense S{S} ns{ns} W{win}")
+
+
 def test_mla_backward_two_latent_heads(gpu_device):
     B, S, Hq, Hkv, ns, win = 2, 70, 128, 2, 4, 20
     q, k, v, dout = _case(gpu_device, B, S, Hq, Hkv, 576, 512, alias=True, seed=30)
