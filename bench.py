@@ -174,11 +174,13 @@ def main() -> int:
             "kernel": "ssa_fwd_kernel<576,512> prefill", "bound": "mfma",
             "achieved": round(prefill_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(prefill_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic["prefill"],
+            "traffic_source": "stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command (profiles/hbm_traffic.json), not measured in this run",
         },
         "roofline_decode": {
             "kernel": "ssa_fwd_kernel<576,512> decode split + merge", "bound": "hbm",
             "achieved": round(decode_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(decode_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic["decode"],
+            "traffic_source": "stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command (profiles/hbm_traffic.json), not measured in this run",
         },
     }
 
@@ -223,6 +225,34 @@ def main() -> int:
             }
             del ws_cal, o_mix, o_full, o_sparse, lse_f
             torch.cuda.empty_cache()
+
+    # ---- engine-shaped calls on the decode's caches: paged decode, chunked prefill ("extend") ----------------
+    if not args.no_comparator:
+        page = 128
+        max_pages = dc.S_max // page
+        pool = kc.view(dc.B * max_pages, page, dc.Hkv, dc.d_qk)   # the contiguous cache seen as pages of 128 rows
+        gen_t = torch.Generator(device=dev).manual_seed(11)
+        # every sequence's pages in a shuffled order of their own (a table that is not the identity)
+        table = torch.stack([torch.randperm(max_pages, generator=gen_t, device=dev) + b * max_pages for b in range(dc.B)]).to(torch.int32)
+        paged_ms = timed(lambda: loza.loza_ssa_decode_paged(dq, pool, pool, table, seqlens, dout, dlse, dc.n_sink, dc.window,
+                                                            dc.scale, ws), 10)
+        q_len, Be = 1024, 8
+        qe = torch.randn(Be, q_len, dc.Hq, dc.d_qk, generator=gen_t, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        oe = torch.empty(Be, q_len, dc.Hq, dc.d_v, dtype=torch.bfloat16, device=dev)
+        le = torch.empty(Be, dc.Hq, q_len, dtype=torch.float32, device=dev)
+        kce = kc[:Be]   # the first sequences' caches (a view: the same object serves as keys and values)
+        ext_ms = timed(lambda: loza.loza_ssa_extend(qe, kce, kce, seqlens[:Be].contiguous(), oe, le, dc.n_sink, dc.window, dc.scale), 5)
+        ext_paged_ms = timed(lambda: loza.loza_ssa_extend_paged(qe, pool, pool, table[:Be].contiguous(), seqlens[:Be].contiguous(), oe, le,
+                                                                dc.n_sink, dc.window, dc.scale), 5)
+        # every query of a chunk sits beyond n_sink + window keys here: n_sink + window live keys each
+        ext_flop = 2.0 * Be * q_len * (dc.n_sink + dc.window) * (dc.d_qk + dc.d_v) * dc.Hq
+        result["engine_shaped"] = {
+            "decode_paged_us": round(paged_ms * 1e3, 1), "decode_paged_vs_contiguous": round(paged_ms / decode_ms, 3),
+            "extend": f"{Be} sequences x {q_len} new tokens against caches of 65536..262144 rows",
+            "extend_ms": round(ext_ms, 3), "extend_tflops": round(ext_flop / (ext_ms * 1e-3) / 1e12, 1),
+            "extend_paged_ms": round(ext_paged_ms, 3),
+        }
+        del qe, oe, le, table
 
     # ---- the paper's own parametrisation on the same tensors: 1 sink block + 7 local blocks of 128 ----
     if not args.no_comparator:
