@@ -103,6 +103,11 @@ struct TileCfg {
     static constexpr int OFF_LPART = OFF_FLAG + 2 * 16;           // float[2][M]
     static constexpr int OFF_REDO = OFF_LPART + 2 * M * 4;        // int: the tile has to be computed again, with two-term P
     static constexpr int LDS_BYTES = OFF_REDO + 16;
+    // The softmax between the matrix instructions of the value phase takes the speculative form (below)
+    // where that phase has a matrix instruction for every one of its jobs; with fewer (narrow values)
+    // the vector ALU is the bound either way and the ordinary form has fewer instructions.
+    static constexpr int SPEC_JOBS = 30;
+    static constexpr bool SPEC_SOFTMAX = !DECODE && (N / 16) * DVB * RB >= SPEC_JOBS;
     static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the 160 KB LDS");
 };
 
@@ -504,6 +509,73 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
 #pragma unroll
         for (int j = 0; j < SM_JOBS; ++j) sm_job(std::false_type{}, j, s, j0, lazy, pbuf);
     };
+    // The same softmax for the value phase of prefill and extend, where the reference almost never
+    // moves: the exponentials are taken against the CURRENT reference at once, without waiting for the
+    // tile's maximum (a serial chain of some thirty instructions through a cross-lane exchange), and
+    // the largest weight is checked afterwards. Measured on gfx950, one wave per SIMD: behind one
+    // 32x32x16 matrix instruction (32 cycles) an exponential and three simple vector instructions
+    // issue for free if none of them waits for the one before (a dependent instruction issues 8
+    // cycles after the one it waits for, an independent one after 4), while a bf16 dot-product
+    // instruction holds up the matrix pipeline for 16 cycles. So every job below is a handful of
+    // instructions that depend on EARLIER jobs only (element e + 1 is scaled while element e - 1 is
+    // exponentiated and the pair before is packed and summed), and the sum of the rounded weights is
+    // taken with shifts and adds. If a weight exceeds the threshold (2^lazy; 2^0 in an exact tile) or a
+    // row has no reference yet, the wave says so (sm_bad, uniform) and the caller takes the tile's scores
+    // again and runs the ordinary softmax: the result is the one the ordinary order gives.
+    constexpr int SPEC_JOBS = C::SPEC_JOBS;
+    bool sm_bad = false;
+    float sm_pm = 0.f, sm_ra = 0.f, sm_rb = 0.f, sm_lo = 0.f, sm_hi = 0.f;
+    auto sm_job_spec = [&](const int j, f32x16 &s, const int j0, const float thresh, const int pbuf) {
+        auto F = [&](int e) { s[e] = __builtin_fmaf(s[e], p.scale_log2, -sm_m_use); };
+        auto E = [&](int e) { s[e] = __builtin_amdgcn_exp2f(s[e]); };
+        if (j == 0) {
+            sm_mask(s, j0);
+            sm_m_use = (m_ref == LOZA_NEG_INF) ? 0.f : m_ref;
+            sm_alpha = 1.0f;
+            sm_up = false;
+            sm_psum = 0.f;
+            sm_pm = 0.f;
+            sm_ra = 0.f;
+            sm_rb = 0.f;
+            F(0);
+            F(1);
+            asm volatile("" : "+v"(s), "+v"(sm_m_use));
+        } else if (j <= 18) {
+            // one exponential, one scaling, and two instructions of a pair whose exponentials are done
+            if (j - 1 < 16) E(j - 1);
+            if (j + 1 < 16) F(j + 1);
+            if (j >= 3 && (j & 1)) {
+                const int i = (j - 3) / 2;
+                sm_pk[i] = pack_bf16(s[2 * i], s[2 * i + 1]);
+                sm_psum += s[2 * i];
+                asm volatile("" : "+v"(sm_pk[i]), "+v"(sm_psum));
+            } else if (j >= 4) {
+                const int i = (j - 4) / 2;
+                sm_psum += s[2 * i + 1];
+                sm_pm = fmaxf(fmaxf(sm_pm, s[2 * i]), s[2 * i + 1]);
+                asm volatile("" : "+v"(sm_psum), "+v"(sm_pm));
+            }
+            asm volatile("" : "+v"(s));
+        } else if (j == 19) {
+            // (not (pm <= thresh): a NaN weight also takes the ordinary path)
+            sm_bad = __any(!(sm_pm <= thresh) || m_ref == LOZA_NEG_INF);
+        } else if (j <= 28) {
+            // the two halves of pair i are widened while those of pair i - 1 are added, on two accumulators
+            const int i = j - 20;
+            if (i >= 1) {
+                sm_ra += sm_lo;
+                sm_rb += sm_hi;
+            }
+            if (i < 8) {
+                sm_lo = __builtin_bit_cast(float, sm_pk[i] << 16);
+                sm_hi = __builtin_bit_cast(float, sm_pk[i] & 0xffff0000u);
+            }
+            if (i == 8) sm_rsum = sm_ra + sm_rb;
+            asm volatile("" : "+v"(sm_ra), "+v"(sm_rb), "+v"(sm_lo), "+v"(sm_hi), "+v"(sm_rsum));
+        } else if (j == 29) {
+            if (__builtin_expect(!sm_bad, 1)) sm_end_fn(pbuf);
+        }
+    };
 
     // ---- accumulator rescale of one tile (rare after the first tiles) -----------------------------------
     auto rescale_flags = [&](const int pbuf) { return *(const u32x4 *)(s_flag + pbuf * 4); };
@@ -563,7 +635,8 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
     };
     auto value_tile = [&](const int stage, const int pbuf, ValueFrags &f, auto with_softmax, f32x16 &s,
                           const int j0_next, const int pbuf_next, const float lazy, auto &&after_slot) {
-        constexpr bool WITH_SOFTMAX = decltype(with_softmax)::value;
+        constexpr int SM_MODE = decltype(with_softmax)::value;   // 0 none, 1 the job list, 2 the speculative job list
+        constexpr bool WITH_SOFTMAX = SM_MODE == 1;
         constexpr int KS = V_KS, NSTEP = V_NSTEP;
         const char *vp, *pb;
         value_ptrs(stage, pbuf, vp, pb);
@@ -600,6 +673,12 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
                     for (int jj = 0; jj < JPS; ++jj)
                         // (two-term pass: the hand-over, the last job, waits for a barrier of its own)
                         if (slot * JPS + jj < SM_JOBS - (PRECISE ? 1 : 0)) sm_job(std::true_type{}, slot * JPS + jj, s, j0_next, lazy, pbuf_next);
+                }
+                if (SM_MODE == 2) {
+                    constexpr int JPS2 = (SPEC_JOBS + NSLOT - 1) / NSLOT;
+#pragma unroll
+                    for (int jj = 0; jj < JPS2; ++jj)
+                        if (slot * JPS2 + jj < SPEC_JOBS) sm_job_spec(slot * JPS2 + jj, s, j0_next, lazy, pbuf_next);   // (lazy: the threshold 2^lazy)
                 }
                 after_slot(slot, NSLOT);
                 __builtin_amdgcn_sched_barrier(0);
@@ -654,6 +733,7 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
     // reads its block table here, and the answer is there when the copies are issued)
     auto tile_ahead = [&](int u) { return t_begin + u + AHEAD < t_end ? t_begin + u + AHEAD : t_end - 1; };
     int32_t page_pre = nt > 0 ? page_request(tile_ahead(0)) : 0;
+    const float lazy_thresh = __builtin_amdgcn_exp2f(p.lazy_log2);
     if (!SPEC) {
         int st_v = 0;  // ring stage of tile u
         for (int u = 0; u < nt; ++u) {
@@ -675,8 +755,23 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
                 score_tile(st_k, s);
             }
             rescale_tile(u & 1, flags);
-            value_tile(st_v, u & 1, vf, std::true_type{}, s, u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff,
-                       (u + 1) & 1, u + 1 < p.exact_tiles ? 0.f : p.lazy_log2, [](int, int) {});
+            {
+                const int j0_next = u + 1 < nt ? key_tile(t_begin + u + 1) * N : 0x3fffffff;
+                const bool exact = u + 1 < p.exact_tiles;
+                if constexpr (PRECISE || !C::SPEC_SOFTMAX) {
+                    value_tile(st_v, u & 1, vf, std::integral_constant<int, 1>{}, s, j0_next, (u + 1) & 1, exact ? 0.f : p.lazy_log2, [](int, int) {});
+                } else {
+                    // (one instantiation of the value phase in the loop: with the ordinary and the
+                    // speculative form side by side the register allocator spills. An exact tile is a
+                    // speculative one with the threshold 2^0.)
+                    value_tile(st_v, u & 1, vf, std::integral_constant<int, 2>{}, s, j0_next, (u + 1) & 1, exact ? 1.0f : lazy_thresh, [](int, int) {});
+                    if (__builtin_expect(sm_bad, 0)) {
+                        // the reference has to move (or the row has none yet): scores again, ordinary softmax
+                        score_tile(st_k, s);
+                        softmax_tile(s, j0_next, (u + 1) & 1, exact ? 0.f : p.lazy_log2);
+                    }
+                }
+            }
             if constexpr (PRECISE) {
                 // every wave has read P of tile u: the single pair of buffers can take P of tile u + 1
                 lds_barrier();
@@ -717,7 +812,7 @@ static __device__ __forceinline__ bool ssa_fwd_tile(const FwdParams &p, char *sm
             const bool more = u + AHEAD < nt;
             const TileCopy tc = plan_copy(more ? t_begin + u + AHEAD : t_begin + u, st_l, row_now);
             rescale_tile(u & 1, flags);
-            value_tile(st_v, u & 1, vf, std::false_type{}, s, 0, 0, 0.f, [&](int slot, int n_slots) {
+            value_tile(st_v, u & 1, vf, std::integral_constant<int, 0>{}, s, 0, 0, 0.f, [&](int slot, int n_slots) {
                 const int per_slot = (COPIES_PER_WAVE + n_slots - 1) / n_slots;
 #pragma unroll
                 for (int c = slot * per_slot; c < (slot + 1) * per_slot; ++c)
@@ -1042,6 +1137,10 @@ static hipError_t launch_prefill_kernel(FwdParams p, hipStream_t stream)
     if (e != hipSuccess) return e;
     p.rt_begin = 0;
     p.all_precise = pattern_needs_precise(p) ? 1 : 0;
+    // The speculative softmax scores a tile twice when the reference moves: the reference is exact
+    // over the first tile only, afterwards lazy (with an exact reference over the first 8 tiles most
+    // of them would move it).
+    if (C::SPEC_SOFTMAX) p.exact_tiles = 1;
     const int64_t blocks = (int64_t)p.row_tiles * p.Hkv * p.B;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), C::LDS_BYTES, stream, p);
     return hipGetLastError();
@@ -1204,3 +1303,4 @@ hipError_t launch_decode_bf16(const FwdParams &p, int d_qk, int d_v, bool alias,
 }
 
 }  // namespace loza
+

@@ -94,3 +94,30 @@ def test_mla_decode_peaked_rows(gpu_device, ns, win, block):
     ref_out, _ = H.oracle_decode(q, kc, kc, seqlens, rb, rh, ns, win, scale, 512, block)
     assert _n_large(ref_out) > 100, "the construction no longer produces large results"
     H.compare_decode(q, kc, kc, seqlens, out, lse, rb, rh, ns, win, scale, f"peaked decode ns{ns} W{win} b{block}", block=block)
+
+
+@pytest.mark.parametrize("S,ns,win", [(640, 128, 300), (600, 0, 2000)])
+def test_mla_prefill_scores_that_keep_rising(gpu_device, S, ns, win):
+    """Scores that grow with the key position by more than the lazy threshold of the online softmax
+    (2^8) per key tile: the reference of every row has to move on almost every tile, so the prefill's
+    softmax between the matrix instructions (which takes its exponentials against the current
+    reference and checks afterwards) has to take its tiles twice throughout. Keys are noise plus a
+    common direction whose weight rises with the position, queries noise plus that direction; the
+    direction lives in the 64 features that are not part of the values, so that the results stay
+    small and come from the once-rounded weights (no two-term pass beyond the first 128 positions)."""
+    g = torch.Generator(device=gpu_device).manual_seed(77)
+    d = torch.zeros(576, device=gpu_device)
+    d[512:] = torch.randn(64, generator=g, device=gpu_device)
+    d = d / d.norm()
+    scale = 192 ** -0.5
+    # score of key j: about scale * 14 * ramp_j = 0.2 (j - S/2) in natural units: 6.4 per tile of 32 keys = 9.2 in log2 units
+    ramp = (torch.arange(S, device=gpu_device, dtype=torch.float32) - S / 2) * (0.2 / (scale * 14.0))
+    k = (0.3 * torch.randn(1, S, 1, 576, generator=g, device=gpu_device) + ramp[None, :, None, None] * d).to(torch.bfloat16)
+    q = (0.3 * torch.randn(1, S, 64, 576, generator=g, device=gpu_device) + 14.0 * d).to(torch.bfloat16)
+    out, lse = H.run_prefill(q, k, k, ns, win, scale, d_v=512)
+    rb, rh, ri = H.all_rows(1, 64, S)
+    ref_out, ref_lse = H.oracle_prefill_rows(q, k, k, rb, rh, ri, ns, win, scale, 512)
+    assert float(np.abs(ref_out).max()) < 1.9, "the construction no longer keeps the results small"
+    deep = ri >= 256
+    assert float(ref_lse[deep].max() - ref_lse[deep].min()) > 60.0, "the construction no longer makes the scores rise"
+    H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, f"rising scores S{S} ns{ns} W{win}")
