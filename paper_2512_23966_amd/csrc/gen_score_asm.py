@@ -161,6 +161,10 @@ if __name__ == "__main__":
         print(macro(dqk))
     print(macro_copy(576, 9, 4))
     print(macro_copy(576, 4, 2, " nt"))
-    for ks, n_a, n_b, n_agpr in ((36, 9, 8, 32), (32, 9, 8, 24), (36, 9, 0, 32), (32, 9, 0, 24)):
+    # key-stationary kernel: 9 + 2 + 1 woven copies (the other 6 of the second sub-tile go out during the
+    # elementwise step; the offset array keeps its 18 entries); row-stationary kernel: 9 + 0 + 1
+    for ks, n_a, n_b, n_agpr in ((36, 9, 2, 32), (32, 9, 2, 24)):
+        print(macro_bwd(ks, n_a, n_b, n_agpr, n_voff=18))
+    for ks, n_a, n_b, n_agpr in ((36, 9, 0, 32), (32, 9, 0, 24)):
         print(macro_bwd(ks, n_a, n_b, n_agpr))
     print("#endif")

@@ -119,6 +119,11 @@ struct BwdCfg {
     static constexpr int NEXTRA = R1 + R2 + NSTAT;
     static_assert(NEXTRA <= 4, "one extra copy instruction per wave at most");
     static constexpr int PER_WAVE = A1 + A2 + 1;
+    // Wide rows, key-stationary kernel: 18 copy instructions per wave between the 36 matrix instructions
+    // of phase 1 are more than the compute unit's memory pipeline takes at that pace (the waves queue
+    // on it); only A2_WOVEN of the second sub-tile's are woven into phase 1, the others go out in pairs
+    // during the elementwise step (measured: in threes slightly worse, in fours much worse).
+    static constexpr int A2_WOVEN = (KEYS && DQK == 576 && DV == 512) ? 2 : A2;
     static constexpr int STAGE = NI * 1024;
     static constexpr int OFF_Y2 = N1 * 1024, OFF_STAT = (N1 + N2) * 1024;
     static constexpr int PROW = 32 * 2 + 16;          // LDS bytes per row of the dS / p buffers
@@ -448,14 +453,14 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             // score phase is: fragment kk + 6 is fetched from LDS while fragment kk feeds the matrix core,
             // with the exact lgkmcnt each step needs, and this wave's copy instructions of the next tile
             // issue between the matrix instructions.
-            static_assert(!WIDE || (C::A1 == 9 && C::A2 == (KEYS ? 8 : 0)), "one asm variant per copy plan");
+            static_assert(!WIDE || (C::A1 == 9 && C::A2 == (KEYS ? 8 : 0) && C::A2_WOVEN == (KEYS ? 2 : 0)), "one asm variant per copy plan");
             static_assert(!WIDE || IN_AGPR == (ROLE == 0 ? 32 : 24), "one asm variant per register split");
             bf16x8 kf[LOZA_SCORE_DEPTH_576];
             uint32_t tmp;
             const uint32_t a_addr = smem_lds + st * C::STAGE + A_OFF + ln * A_ROW + lh * 16;
             if constexpr (KEYS) {
-                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_A9_B8_G32(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
-                else LOZA_BWD_PHASE1_K32_A9_B8_G24(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
+                if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_A9_B2_G32(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
+                else LOZA_BWD_PHASE1_K32_A9_B2_G24(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
             } else {
                 if constexpr (ROLE == 0) LOZA_BWD_PHASE1_K36_A9_B0_G32(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
                 else LOZA_BWD_PHASE1_K32_A9_B0_G24(c, kf, tmp, a_addr, xf, yoff, tc, wave, C::NEXTRA);
@@ -499,7 +504,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         }
     };
     // (tile `t_idx` of this work item, in stage `st`)
-    auto elementwise_step = [&](const f32x16 &c, const int t_idx, const int st) {
+    auto elementwise_step = [&](const f32x16 &c, const int t_idx, const int st, const TileCopy &tc) {
         const char *tile = smem + st * C::STAGE;
         // ---- elementwise: p = exp2(scale log2e s - lse log2e), dS = scale p (T - D), masked ----------
         // four values at a time: this lane's 16 values are four runs of four consecutive y, and a run
@@ -528,6 +533,14 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
             }
             // (everything this step reads from LDS is requested before the first result is written back:
             // a read behind a write would wait for it, and the wave has nothing to hide that behind)
+            // (the copy instructions of the second sub-tile that phase 1 left out: two now, two after each half)
+            constexpr int LATE = C::A2 - C::A2_WOVEN, LATE_STEP = (LATE + 2) / 3;
+            auto late_copies = [&](int part) {
+#pragma unroll
+                for (int cc = part * LATE_STEP; cc < (part + 1) * LATE_STEP; ++cc)
+                    if (cc < LATE) issue_one(tc, C::A1 + C::A2_WOVEN + cc);
+            };
+            late_copies(0);
             float4 o4[2];
             float2 sd[2][4];
 #pragma unroll
@@ -565,6 +578,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
                     pv[t] = ok ? pe : 0.f;
                     dsv[t] = ok ? p.scale * pe * (tv - D) : 0.f;
                 }
+                late_copies(1 + q2);
                 u32x2 w;
                 w[0] = pack_bf16(dsv[0], dsv[1]);
                 w[1] = pack_bf16(dsv[2], dsv[3]);
@@ -641,7 +655,7 @@ __global__ __launch_bounds__(256) void ssa_bwd_kernel(const BwdParams p)
         phase1(st, tc, c);
         hand_over(c);
         __syncthreads();
-        elementwise_step(c, u, st);
+        elementwise_step(c, u, st, tc);
         __syncthreads();
         phase2(st);
     }
