@@ -40,6 +40,10 @@ def main() -> int:
     ap.add_argument("--only", choices=["cfg2"], default=None,
                     help="profiling aid: launch just this workload --steps times (after --warmup untimed launches) "
                          "and print its time; cfg2 = the 32K-token MHA prefill (d = 128)")
+    ap.add_argument("--constant-inputs", action="store_true",
+                    help="profiling aid: the timed prefill gets constant q and k instead of random ones (the same "
+                         "instructions with operands that do not toggle: shows what part of the launch time is the "
+                         "clock the chip sustains under the switching activity of real data); says so in `data`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB -> 1 GiB elementwise copy kernel (what HBM byte counters "
                          "collected with rocprofv3 --pmc are scaled by)")
@@ -86,6 +90,9 @@ def main() -> int:
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
     q, k, v = W.make_prefill_inputs(pc, dev)
+    if args.constant_inputs:
+        q.fill_(1.0)
+        k.fill_(0.001)
     out = torch.empty(pc.B, pc.S, pc.Hq, pc.d_v, dtype=pc.dtype, device=dev)
     lse = torch.empty(pc.B, pc.Hq, pc.S, dtype=torch.float32, device=dev)
     dq, kc, vc, seqlens = W.make_decode_inputs(dc, dev)
@@ -159,7 +166,7 @@ def main() -> int:
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if not args.constant_inputs else "constant q and k (clock probe, not the benchmark's data)",
         "config": {
             "workload": "MLA absorbed SSA prefill bf16 B=1 Hq=64 Hkv=1 S=131072 d_qk=576 d_v=512 n_sink=128 window=8192 "
                         "+ MLA SSA decode bf16 B=64 Hq=64 cache lengths U[65536,262144] (one step = one prefill + one decode)",
@@ -323,6 +330,27 @@ def main() -> int:
             "cores": threads, "kind": "oracle",
             "sample": f"{n} seeded random (position, head) rows of the 128K prefill with the full {pc.n_sink + pc.window}-key live set, "
                       f"{t_cpu:.1f} s; whole prefill would take {prefill_flop / (cpu_flop / t_cpu) / 3600:.1f} h",
+        }
+
+    # ---- the timed prefill once more with constant q and k (outside the timed step) ----------------------
+    # Same launch, same instruction stream (every weight of a row is equal, nothing is rescaled), operands that
+    # do not toggle: the difference to the timed launch is the clock the chip sustains under the switching
+    # activity of random operands, i.e. the part of the gap to the matrix peak that no schedule recovers.
+    if not args.no_comparator and not args.constant_inputs:
+        q.fill_(1.0)
+        k.fill_(0.001)
+        prefill(); torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ea.record(); prefill(); eb.record(); torch.cuda.synchronize()
+            ts.append(ea.elapsed_time(eb))
+        const_ms = float(np.median(ts))
+        result["operand_activity"] = {
+            "workload": "the timed prefill launch with q = 1 and k = 0.001 everywhere (not the benchmark's data)",
+            "prefill_ms_constant_inputs": round(const_ms, 3),
+            "mfma_frac_constant_inputs": round(prefill_flop / (const_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "random_over_constant": round(prefill_ms / const_ms, 3),
         }
 
     # ---- the other prefill configurations (outside the timed step): 32K MHA and 1M-token MLA -------------
