@@ -121,3 +121,25 @@ def test_mla_prefill_scores_that_keep_rising(gpu_device, S, ns, win):
     deep = ri >= 256
     assert float(ref_lse[deep].max() - ref_lse[deep].min()) > 60.0, "the construction no longer makes the scores rise"
     H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, f"rising scores S{S} ns{ns} W{win}")
+
+
+def test_mla_prefill_score_jump_that_overflows_the_speculative_weights(gpu_device):
+    """Scores that jump by 100 (144 in log2 units) from one key to the next: weights taken against the
+    reference of the keys before the jump overflow fp32 (2^128), which the prefill's speculative softmax
+    has to notice (an infinite largest weight) and answer by taking the tile again in the ordinary order.
+    Same construction as above with a step instead of a ramp: scores of -55 before key 400, +45 from it on."""
+    S, ns, win, j_step = 640, 128, 300, 400
+    g = torch.Generator(device=gpu_device).manual_seed(78)
+    d = torch.zeros(576, device=gpu_device)
+    d[512:] = torch.randn(64, generator=g, device=gpu_device)
+    d = d / d.norm()
+    scale = 192 ** -0.5
+    level = torch.where(torch.arange(S, device=gpu_device) < j_step, -55.0, 45.0) / (scale * 14.0)
+    k = (0.3 * torch.randn(1, S, 1, 576, generator=g, device=gpu_device) + level[None, :, None, None] * d).to(torch.bfloat16)
+    q = (0.3 * torch.randn(1, S, 64, 576, generator=g, device=gpu_device) + 14.0 * d).to(torch.bfloat16)
+    out, lse = H.run_prefill(q, k, k, ns, win, scale, d_v=512)
+    rb, rh, ri = H.all_rows(1, 64, S)
+    ref_out, ref_lse = H.oracle_prefill_rows(q, k, k, rb, rh, ri, ns, win, scale, 512)
+    assert float(np.abs(ref_out).max()) < 1.9, "the construction no longer keeps the results small"
+    assert float(ref_lse[ri >= j_step].min() - ref_lse[(ri >= 256) & (ri < j_step)].max()) > 80.0, "the construction no longer makes the scores jump past 2^128"
+    H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, "score jump past the fp32 range")
