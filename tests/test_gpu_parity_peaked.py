@@ -143,3 +143,21 @@ def test_mla_prefill_score_jump_that_overflows_the_speculative_weights(gpu_devic
     assert float(np.abs(ref_out).max()) < 1.9, "the construction no longer keeps the results small"
     assert float(ref_lse[ri >= j_step].min() - ref_lse[(ri >= 256) & (ri < j_step)].max()) > 80.0, "the construction no longer makes the scores jump past 2^128"
     H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, "score jump past the fp32 range")
+
+
+def test_mla_extend_scores_that_keep_rising(gpu_device):
+    """The rising scores of the prefill case above through the extend entry point (its own instantiation
+    of the tile kernel): 300 new tokens against caches of 640 and 500 rows."""
+    B, S_max, q_len, lens, ns, win = 2, 640, 300, [640, 500], 128, 300
+    g = torch.Generator(device=gpu_device).manual_seed(79)
+    d = torch.zeros(576, device=gpu_device)
+    d[512:] = torch.randn(64, generator=g, device=gpu_device)
+    d = d / d.norm()
+    scale = 192 ** -0.5
+    ramp = (torch.arange(S_max, device=gpu_device, dtype=torch.float32) - S_max / 2) * (0.2 / (scale * 14.0))
+    kc = (0.3 * torch.randn(B, S_max, 1, 576, generator=g, device=gpu_device) + ramp[None, :, None, None] * d).to(torch.bfloat16)
+    q = (0.3 * torch.randn(B, q_len, 64, 576, generator=g, device=gpu_device) + 14.0 * d).to(torch.bfloat16)
+    seqlens = torch.tensor(lens, dtype=torch.int32, device=gpu_device)
+    out, lse = E._run(q, kc, kc, seqlens, (ns, win), scale, 512, None)
+    E._compare(q, kc, kc, lens, out, lse, (ns, win), scale, "rising scores, extend", None)
+    assert float(out.float().abs().max()) < 1.9, "the construction no longer keeps the results small"
