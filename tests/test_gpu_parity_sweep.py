@@ -44,6 +44,28 @@ def test_mla_prefill_sweep(gpu_device, case):
     H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, f"sweep {case}: B{B} S{S} ns{ns} W{win} b{block}", block=block)
 
 
+@pytest.mark.parametrize("case", range(500, 512))
+def test_mla_prefill_hot_scores_sweep(gpu_device, case):
+    """Longer sequences with queries three times as large: the scores spread over +-25, so that the reference
+    of the online softmax moves on many tiles well past the first 128 positions (the speculative softmax of
+    the prefill has to fall back again and again, on some waves of a tile and not on others) and many rows
+    are dominated by one key (large results: the two-term pass takes those tiles)."""
+    r = np.random.default_rng(1000 + case)
+    S = int(r.integers(300, 900))
+    ns = int(r.choice([0, 4, 128, 200]))
+    win = int(r.choice([64, 300, 1000]))
+    block = [None, None, 32][case % 3]
+    if block is not None:
+        ns, win = ns // 64, max(1, win // 64)
+    B = 1 + case % 2
+    q = (_rand((B, S, 64, 576), 7000 + case, gpu_device).float() * 3.0).to(torch.bfloat16)
+    k = _rand((B, S, 1, 576), 8000 + case, gpu_device)
+    scale = 192 ** -0.5
+    out, lse = H.run_prefill(q, k, k, ns, win, scale, d_v=512, block=block)
+    rb, rh, ri = H.all_rows(B, 64, S)
+    H.compare_prefill(q, k, k, out, lse, rb, rh, ri, ns, win, scale, f"hot sweep {case}: B{B} S{S} ns{ns} W{win} b{block}", block=block)
+
+
 @pytest.mark.parametrize("case", range(100, 116))
 def test_d128_prefill_sweep(gpu_device, case):
     S, ns, win, block = _pattern(case)
